@@ -1,0 +1,210 @@
+"""Pins for the oracle's search (Alg. 2, Sec. 3.3), RobustPrune (Eq. 1) and sequential build.
+
+The traversal a heuristic search takes has no closed form, so the search is pinned
+through what the paper and the mathematics do fix: degenerate settings that reduce
+to textbook best-first search and to exact k-NN, the structural invariants of
+Alg. 2, the seen-set invariant, and recall against brute force.
+"""
+import heapq
+
+import numpy as np
+import pytest
+
+import pag_workloads as wl
+
+
+def _knn_graph_index(orc, base, deg, P, seed=3):
+    """An index over an exact k-NN graph (graph quality is not under test here)."""
+    n, d = base.shape
+    rot = orc.make_transform(d, seed)
+    cb = orc.make_codebooks(d, P, seed)
+    vec = np.stack([orc.rotate(rot, x) for x in base])
+    nbr, _ = wl.brute_force(vec, vec, min(deg + 1, n))
+    adj = np.full((n, deg), orc.EMPTY, np.uint32)
+    for i in range(n):
+        row = [j for j in nbr[i] if j != i][:deg]
+        adj[i, :len(row)] = row
+    ix = orc.OracleIndex(vec, adj, np.zeros((n, deg), np.float32), np.zeros((n, deg), np.float32),
+                         np.zeros((n, deg), np.float32), np.zeros((n, deg, P), np.uint8), rot, cb,
+                         np.arange(min(n, 1024), dtype=np.uint32))
+    codes, a, c, e2 = ix.recompute_edge_info()
+    ix.codes[:], ix.a[:], ix.c[:], ix.e2[:] = codes, a, c, e2
+    return ix
+
+
+def _textbook_beam_search(vec, adj, q, entry, ef):
+    """Best-first search with one bounded priority queue, as described for graph indexes in
+    Appendix C.1.2: expand the closest unvisited node of the queue, push its neighbours, stop
+    when every queue member is visited."""
+    def dist(i):
+        df = (q - vec[i]).astype(np.float32)
+        return np.float32((df.astype(np.float64) ** 2).sum())
+    seen = set(int(e) for e in entry)
+    pool = sorted((dist(e), int(e), False) for e in entry)      # (dist, id, visited)
+    while True:
+        nxt = next((k for k, p in enumerate(pool) if not p[2]), None)
+        if nxt is None:
+            break
+        dist_u, u, _ = pool[nxt]
+        pool[nxt] = (dist_u, u, True)
+        news = []
+        for w in adj[u]:
+            w = int(w)
+            if w == 0xFFFFFFFF or w in seen:
+                continue
+            seen.add(w)
+            news.append((dist(w), w, False))
+        pool = sorted(pool + news)[:ef]
+    return pool
+
+
+def test_complete_graph_without_test_is_exact_knn(orc):
+    rng = np.random.default_rng(1)
+    n, d, P, K = 40, 16, 4, 5
+    base = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((30, d)).astype(np.float32)
+    ix = _knn_graph_index(orc, base, deg=n - 1, P=P)
+    ids, dists, _ = ix.search(q, K, efS=n, b=n, flags=orc.NO_PRT)
+    gt, gk = wl.brute_force(ix.vec, np.stack([orc.rotate(ix.rot, x) for x in q]), K)
+    assert np.array_equal(ids, gt)
+    assert np.allclose(dists, gk, rtol=1e-6)
+
+
+def test_single_pool_without_test_is_textbook_best_first(orc):
+    """b = efS (one round, W is the whole queue) and no projection test."""
+    rng = np.random.default_rng(2)
+    n, d, P, deg, K, ef = 600, 24, 3, 8, 10, 24
+    base = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((25, d)).astype(np.float32)
+    ix = _knn_graph_index(orc, base, deg, P)
+    ids, dists, ctr = ix.search(q, K, efS=ef, b=ef, flags=orc.NO_PRT)
+    assert ctr["rounds"] == len(q)
+    qr, _ = ix.prepare(q)
+    for r in range(len(q)):
+        pool = _textbook_beam_search(ix.vec, ix.adj, qr[r], ix.entry[:ef], ef)
+        assert [p[1] for p in pool[:K]] == ids[r].tolist()
+        assert np.array_equal(np.array([p[0] for p in pool[:K]], np.float32), dists[r])
+
+
+@pytest.mark.parametrize("flags", [0, 1])
+def test_output_is_topk_of_seen_set_and_structure(orc, cfg1_small, cfg1_oracle_index, flags):
+    """With b >= K every node that leaves W is worse than b nodes that reach R_L at the round's
+    end, so the answer is the top-K by (dist, id) of all nodes whose exact distance was computed.
+    Also: rounds <= ceil(efS / b), no node's exact distance is computed twice."""
+    w, base, q, gt, gtk = cfg1_small
+    ix = cfg1_oracle_index
+    K, efS = 10, 48
+    ids, dists, ctr, seen = ix.search(q, K, efS, flags=flags, want_seen=True)
+    qr, _ = ix.prepare(q)
+    assert ctr["rounds"] <= len(q) * ((efS + 9) // 10)
+    assert ctr["exact"] == sum(len(s) for s in seen)
+    assert ctr["passes"] <= ctr["tests"]
+    for r in range(len(q)):
+        s = seen[r]
+        assert len(set(s.tolist())) == len(s)
+        keys = np.array([orc.key(qr[r], ix.vec[i]) for i in s], np.float32)
+        order = np.lexsort((s, keys))[:K]
+        assert s[order].tolist() == ids[r].tolist()
+        assert np.array_equal(keys[order], dists[r])
+        assert np.all(np.diff(dists[r]) >= 0)
+
+
+def test_recall_against_brute_force(orc, cfg1_small, cfg1_oracle_index):
+    """Problem statement (Sec. 1): recall@K against exact K-NN; rises with efS; the literal reading
+    of the neighbour loop and the hop-synchronous one give the same recall within 0.005."""
+    w, base, q, gt, gtk = cfg1_small
+    ix = cfg1_oracle_index
+    rec = []
+    for efS in (10, 32, 64, 128):
+        ids, dists, ctr = ix.search(q, w.K, efS)
+        rec.append(wl.recall_at_k(ids, gt))
+    assert rec[0] < rec[1] < rec[2] <= rec[3] + 0.002
+    assert rec[2] >= 0.95
+    ids_l, _, _ = ix.search(q, w.K, 64, flags=orc.LITERAL)
+    assert abs(wl.recall_at_k(ids_l, gt) - rec[2]) < 0.005
+    # reported distances are the true squared distances of the returned ids (rotation is orthogonal)
+    ids, dists, _ = ix.search(q, w.K, 64)
+    true = ((base[ids].astype(np.float64) - q[:, None, :].astype(np.float64)) ** 2).sum(-1)
+    assert np.allclose(dists, true, rtol=2e-5)
+
+
+def test_test_skips_most_exact_distances(orc, cfg1_small, cfg1_oracle_index):
+    """Sec. 4.2: the ratio gamma of tested neighbours that get an exact distance is small
+    (real data: generally below 0.2; this low-dimensional synthetic set: below 0.5), and the
+    search still computes fewer exact distances than the same search without the test."""
+    w, base, q, gt, gtk = cfg1_small
+    ix = cfg1_oracle_index
+    _, _, c = ix.search(q, w.K, 64)
+    _, _, c0 = ix.search(q, w.K, 64, flags=orc.NO_PRT)
+    assert c["passes"] / c["tests"] < 0.5
+    assert c["exact"] < 0.75 * c0["exact"]
+
+
+def test_ip_and_cos_keys(orc):
+    """Unit vectors: the reported key is 1 - <q, x> = ||q-x||^2 / 2 and COS normalises the query."""
+    w = wl.workload(2, n=1500, nq=40)
+    w = w.__class__(**{**w.__dict__, "d": 64, "P": 8})
+    base = wl.make(w, "base")
+    q = wl.make(w, "query")
+    ix = orc.OracleIndex.build(base, wl.IP, deg=16, P=8, efC=64, seed=5)
+    ids, dists, _ = ix.search(q, 5, 64)
+    ip = np.einsum("qkd,qd->qk", base[ids].astype(np.float64), q.astype(np.float64))
+    assert np.allclose(dists, 1.0 - ip, atol=2e-6)
+    ixc = orc.OracleIndex(ix.vec, ix.adj, ix.a, ix.c, ix.e2, ix.codes, ix.rot, ix.cb, ix.entry, metric=wl.COS)
+    ids_c, dists_c, _ = ixc.search(3.0 * q, 5, 64)
+    assert np.array_equal(ids_c, ids)
+    assert np.allclose(dists_c, dists, atol=1e-6)
+
+
+def test_robust_prune_definition(orc):
+    """Eq. 1 with alpha = 1 on hand-made planar points: v at the origin; candidates on one ray are
+    reduced to the nearest; a candidate in the opposite direction survives."""
+    pts = np.zeros((6, 4), np.float32)
+    pts[1, 0], pts[2, 0], pts[3, 0] = 1.0, 2.0, 3.0        # same ray
+    pts[4, 0] = -2.5                                        # opposite ray
+    pts[5, :2] = (0.0, 2.2)                                 # orthogonal
+    n, d, deg, P = 6, 4, 4, 2
+    ix = orc.OracleIndex(pts, np.full((n, deg), orc.EMPTY, np.uint32), np.zeros((n, deg), np.float32),
+                         np.zeros((n, deg), np.float32), np.zeros((n, deg), np.float32),
+                         np.zeros((n, deg, P), np.uint8), np.eye(d, dtype=np.float32),
+                         orc.make_codebooks(d, P, 1), np.arange(n, dtype=np.uint32))
+    cand = np.array([1, 2, 5, 4, 3], np.uint32)
+    keys = np.array([orc.key(pts[0], pts[i]) for i in cand], np.float32)
+    assert np.all(np.diff(keys) >= 0)
+    kept, kk = ix.robust_prune(cand, keys, deg)
+    assert kept.tolist() == [1, 5, 4]
+    # property form on random points: every dropped candidate has a kept, closer-to-v witness
+    rng = np.random.default_rng(4)
+    pts = rng.standard_normal((60, 8)).astype(np.float32)
+    ix = orc.OracleIndex(pts, np.full((60, deg), orc.EMPTY, np.uint32), np.zeros((60, deg), np.float32),
+                         np.zeros((60, deg), np.float32), np.zeros((60, deg), np.float32),
+                         np.zeros((60, deg, 2), np.uint8), np.eye(8, dtype=np.float32),
+                         orc.make_codebooks(8, 2, 1), np.arange(60, dtype=np.uint32))
+    keys = np.array([orc.key(pts[0], pts[i]) for i in range(1, 60)], np.float32)
+    order = np.lexsort((np.arange(1, 60), keys))
+    cand, keys = (np.arange(1, 60)[order]).astype(np.uint32), keys[order]
+    kept, kk = ix.robust_prune(cand, keys, 59)
+    kept_l = kept.tolist()
+    for c, kc in zip(cand.tolist(), keys.tolist()):
+        occluded = any(orc.key(pts[s], pts[c]) <= kc for s in kept_l
+                       if s != c and (c not in kept_l or kept_l.index(s) < kept_l.index(c)))
+        assert (c in kept_l) == (not occluded)
+    short, _ = ix.robust_prune(cand, keys, 3)
+    assert short.tolist() == kept_l[:3]
+
+
+def test_sequential_build_graph_is_valid(orc, cfg1_small, cfg1_oracle_index):
+    ix = cfg1_oracle_index
+    n = ix.n
+    valid = ix.adj != orc.EMPTY
+    assert ix.adj[valid].max() < n
+    rows = np.arange(n)[:, None].repeat(ix.deg, 1)
+    assert not np.any(ix.adj[valid] == rows[valid])               # no self loops
+    for u in range(0, n, 97):
+        nb = ix.adj[u][valid[u]]
+        assert len(set(nb.tolist())) == len(nb)                    # no duplicate neighbours
+    assert valid.sum(1).min() >= 1
+    # stored inference information equals a fresh evaluation from the vectors
+    codes, a, c, e2 = ix.recompute_edge_info(0, 200)
+    assert np.array_equal(codes, ix.codes[:200])
+    assert np.array_equal(a, ix.a[:200]) and np.array_equal(c, ix.c[:200]) and np.array_equal(e2, ix.e2[:200])
