@@ -1,0 +1,183 @@
+/*
+ * pag.h -- C ABI of the MI355X (gfx950) PAG library.
+ *
+ * PAG (Projection-Augmented Graph) answers approximate K-nearest-neighbour
+ * queries over a dataset D of n vectors in R^d (problem statement, Sec. 1) with
+ * a best-first search over a proximity graph in which a projection-based test
+ * (PRT, Eq. 3, with the Test-Feedback-Buffer threshold of Eq. 4) decides which
+ * neighbours get an exact distance (Alg. 2).  The index is built by inserting
+ * the vectors with that same search followed by RobustPrune (Alg. 1, Step 1;
+ * Eq. 1).
+ *
+ * Conventions for every entry point
+ *   - "dev" pointers are device (HBM) pointers of the GPU that was current when
+ *     the index was created; "host" pointers are ordinary host memory.  All
+ *     buffers are row-major, contiguous and owned by the caller: the library
+ *     never frees them and copies whatever it keeps, so they may be released
+ *     as soon as the call returns.
+ *   - Work is enqueued on pag_params.stream (a hipStream_t, NULL = the null
+ *     stream) and every call returns after that stream has been synchronised.
+ *   - Return value: PAG_OK (0) or a negative pag_status; pag_last_error()
+ *     returns a thread-local, human readable description of the last failure.
+ *     No exception crosses this boundary.
+ *   - Node ids are the row numbers of the vectors in insertion order.
+ */
+#ifndef PAG_H
+#define PAG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pag_index pag_index; /* opaque; created by pag_build / pag_import, destroyed by pag_free */
+
+typedef enum { PAG_L2 = 0, PAG_IP = 1, PAG_COS = 2 } pag_metric;
+
+typedef enum {
+    PAG_OK = 0,
+    PAG_EINVAL = -1,       /* null / inconsistent argument, d % num_subspaces != 0, K == 0, K > n ... */
+    PAG_ECAPACITY = -2,    /* pag_insert beyond pag_params.capacity */
+    PAG_ENOMEM = -3,       /* host or device allocation failed */
+    PAG_EHIP = -4,         /* a HIP call failed; text in pag_last_error() */
+    PAG_EUNSUPPORTED = -5  /* a size outside what the kernels are built for (see pag_params) */
+} pag_status;
+
+/*
+ * Index parameters (Alg. 1 inputs; Appendix D).  Names in brackets are the
+ * paper's.  Limits of this build: d % 4 == 0, d <= 3072, num_subspaces <= 64,
+ * d % num_subspaces == 0, max_degree <= 64, working-set size b <= 128.
+ */
+typedef struct {
+    uint32_t struct_size;     /* sizeof(pag_params), for ABI checking */
+    int32_t  metric;          /* pag_metric.  PAG_IP expects unit-norm vectors (it ranks like PAG_COS
+                                 without normalising); PAG_COS normalises base vectors and queries. */
+    uint32_t max_degree;      /* [2M] maximum out-degree */
+    uint32_t num_subspaces;   /* [L] number of subspaces of the rotated space; 16 projection vectors each */
+    uint32_t ef_construction; /* [efC] nodes visited per insertion; W has min(efC, 100) nodes while indexing */
+    uint32_t search_b;        /* working-set size b = |W| when searching; 0 = max(10, K) (Alg. 2) */
+    uint32_t insert_subbatch; /* vectors inserted concurrently per step of the batch-synchronous build; 0 = auto */
+    uint32_t flags;           /* PAG_FLAG_* */
+    uint64_t capacity;        /* maximum number of vectors including later pag_insert calls; 0 = n */
+    uint64_t seed;            /* seed of the random transform Q and of the codebooks */
+    void*    stream;          /* hipStream_t; NULL = null stream */
+} pag_params;
+
+#define PAG_FLAG_NO_PRT 1u    /* ablation: skip the projection test, every unseen neighbour gets an exact distance */
+
+/*
+ * Flat host view of an index (Alg. 1 output: node set, edge set E, inference
+ * structure I, transform Q, codebooks).  Used by pag_export (the library fills
+ * caller-allocated arrays) and pag_import (the library copies from them).
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  metric;
+    uint64_t n;
+    uint32_t d;
+    uint32_t num_subspaces;   /* P */
+    uint32_t max_degree;      /* deg */
+    uint32_t n_entry;
+    float*    vectors;   /* host [n*d]        base vectors after normalisation (COS) and rotation by Q */
+    uint32_t* adj;       /* host [n*deg]      out-neighbour ids; 0xFFFFFFFF = free slot */
+    float*    a;         /* host [n*deg]      a_i = ||w_i-u|| / cos(beta_i)            (Sec. 3.1) */
+    float*    c;         /* host [n*deg]      c_i = ||w_i-u||^2 + 2 a_i sum_l <u_l, r*_il>  (stored offsets, Appendix C) */
+    float*    e2;        /* host [n*deg]      ||w_i-u||^2 */
+    uint8_t*  codes;     /* host [n*deg*P]    index (0..15) of the selected reference vector per subspace */
+    float*    rotation;  /* host [d*d]        Q, row-major; rotated = Q x */
+    float*    codebooks; /* host [P*16*(d/P)] projection vectors r_jl, norm 1/sqrt(P) */
+    uint32_t* entry;     /* host [n_entry]    entry node ids; a search starts from the first b of them */
+} pag_arrays;
+
+/* Sums over all pag_search calls since creation or the last pag_reset_counters (Sec. 4.2's quantities). */
+typedef struct {
+    uint32_t struct_size;
+    uint32_t adj_record_bytes;   /* size of one node's adjacency record in HBM */
+    uint64_t queries;
+    uint64_t hops;               /* expanded nodes (n' of Sec. 4.2) */
+    uint64_t tests;              /* neighbours submitted to the projection test */
+    uint64_t passes;             /* of those, how many passed (gamma = passes / tests) */
+    uint64_t exact;              /* exact distances computed, entry nodes included */
+    uint64_t rounds;             /* TFB rounds */
+    uint64_t rf_overflow;        /* entries overwritten in the ring R_F */
+    uint64_t rt_overflow;        /* entries overwritten in the ring R_T */
+    uint64_t seen_spills;        /* seen-set insertions that went to the HBM bitmap instead of LDS */
+    double   last_search_kernel_ms; /* HIP-event time of the search kernel of the last pag_search */
+    double   last_prepare_ms;       /* HIP-event time of rotation + projection tables of the last pag_search */
+    double   last_build_ms;         /* wall time of the last pag_build / pag_insert */
+} pag_counters;
+
+/*
+ * pag_build (Alg. 1, Step 1, batch-synchronous): creates an index over the n
+ * vectors D (dev, float32 [n*d]).  D is normalised (PAG_COS), rotated by Q and
+ * copied into the index.  *out receives the handle.
+ */
+int pag_build(const float* D, uint64_t n, uint32_t d, const pag_params* params, pag_index** out);
+
+/*
+ * pag_search (Alg. 2): K approximate nearest neighbours of each of the nq
+ * queries Q (dev, float32 [nq*d]).  efS is the paper's efS: the number of TFB
+ * rounds is ceil(efS / b).  Outputs (dev): ids int64 [nq*K], dists float32
+ * [nq*K], per query ascending by (dist, id).  dists holds squared Euclidean
+ * distances for PAG_L2 and 1 - <q,x> (= ||q-x||^2 / 2 on unit vectors) for
+ * PAG_IP / PAG_COS.  Slots beyond the number of nodes reached hold id -1,
+ * dist +inf.
+ */
+int pag_search(const pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uint32_t efS,
+               int64_t* ids, float* dists);
+
+/*
+ * pag_insert (online insertion, Sec. 4.1): appends the m vectors X (dev,
+ * float32 [m*d]); they receive ids n .. n+m-1.  PAG_ECAPACITY if n + m exceeds
+ * pag_params.capacity.
+ */
+int pag_insert(pag_index* ix, const float* X, uint64_t m);
+
+int pag_free(pag_index* ix);
+
+/* Fills n, d, num_subspaces, max_degree, n_entry, metric of `out` (pointers untouched). */
+int pag_describe(const pag_index* ix, pag_arrays* out);
+/* Copies the index into the caller-allocated host arrays of `out` (sizes as reported by pag_describe). */
+int pag_export(const pag_index* ix, pag_arrays* out);
+/* Creates an index from host arrays (all of them required); params gives capacity, efC, search_b, seed, stream. */
+int pag_import(const pag_arrays* in, const pag_params* params, pag_index** out);
+
+int pag_get_counters(const pag_index* ix, pag_counters* out);
+int pag_reset_counters(pag_index* ix);
+/* Changes search-time settings of an existing index: working-set size (0 = max(10,K)) and PAG_FLAG_* bits. */
+int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t flags);
+/* log2 of the per-query LDS seen-set capacity; 0 = choose from efS.  Small values exercise the HBM spill path. */
+int pag_set_seen_capacity_log2(pag_index* ix, uint32_t log2_slots);
+
+/*
+ * Single steps of the search, exposed for kernel-level parity checks.
+ *
+ * pag_prepare_queries (Alg. 2, "q <- Qq" and "build a projection table"):
+ *   q_rot (dev float32 [nq*d]) and tables (dev float32 [nq*P*16],
+ *   tables[i][l][j] = <q_l, r_jl>) of the queries Q (dev).
+ * pag_exact_distances (Alg. 2, "compute the distance between q and w"):
+ *   keys[i*m+j] = ||q_rot[i] - x[ids[i*m+j]]||^2 for already rotated queries;
+ *   ids dev uint32 [nq*m] (each < n), keys dev float32 [nq*m].
+ * pag_screen (Eq. 3 + Eq. 4 in estimate form): for query i expanding node
+ *   u[i] at squared distance Du[i], est[i*deg+s] = Du + c_s - 2 a_s S_s for
+ *   every neighbour slot s of u[i] (NaN for a free slot); a neighbour passes
+ *   the test iff est < ||z_max - q||^2.  tables as produced above.
+ * pag_edge_info (Sec. 3.1 / Appendix B): recomputes codes, a, c, e2 of every
+ *   stored edge of nodes [node_begin, node_end) from the vectors; outputs are
+ *   host arrays [(node_end-node_begin)*deg (*P)].
+ */
+int pag_prepare_queries(const pag_index* ix, const float* Q, uint64_t nq, float* q_rot, float* tables);
+int pag_exact_distances(const pag_index* ix, const float* q_rot, uint64_t nq, const uint32_t* ids,
+                        uint32_t m, float* keys);
+int pag_screen(const pag_index* ix, const float* tables, uint64_t nq, const uint32_t* u,
+               const float* Du, float* est);
+int pag_edge_info(const pag_index* ix, uint64_t node_begin, uint64_t node_end, uint8_t* codes,
+                  float* a, float* c, float* e2);
+
+const char* pag_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAG_H */

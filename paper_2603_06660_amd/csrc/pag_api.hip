@@ -1,0 +1,602 @@
+// C ABI of the PAG library: argument checking, index life cycle, import / export, and the
+// host side of pag_search (Alg. 2) -- everything that computes runs in the kernels.
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "pag_internal.h"
+
+static thread_local std::string g_last_error;
+void pag_set_error(const std::string& msg) { g_last_error = msg; }
+extern "C" const char* pag_last_error(void) { return g_last_error.c_str(); }
+
+#define PAG_CHECK(cond, code, msg)                 \
+    do {                                           \
+        if (!(cond)) { pag_set_error(msg); return (code); } \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------------
+// Random structures of the method, drawn on the host once per index (Sec. 3.1; Alg. 1):
+// the orthogonal transform Q from the Haar measure (Gaussian matrix, Gram-Schmidt with
+// re-orthogonalisation) and, per subspace, independently rotated cross-polytopes.
+// Counter-based generator: SplitMix64 on (seed, stream, counter) + Box-Muller.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+struct Rng {
+    uint64_t state;
+    explicit Rng(uint64_t seed, uint64_t stream) : state(seed * 0x9E3779B97F4A7C15ull + stream * 0xD1B54A32D192ED03ull + 0x2545F4914F6CDD1Dull) {}
+    uint64_t next() {
+        uint64_t z = (state += 0x9E3779B97F4A7C15ull);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }
+    double uniform() { return ((double)(next() >> 11) + 0.5) * (1.0 / 9007199254740992.0); }
+    double normal() {
+        const double u1 = uniform(), u2 = uniform();
+        return std::sqrt(-2.0 * std::log(u1)) * std::cos(6.283185307179586476925 * u2);
+    }
+};
+
+// Orthonormalise the columns of the dim x dim Gaussian matrix g (column-major) in place.
+void orthonormalise(std::vector<double>& g, uint32_t dim, unsigned threads) {
+    std::vector<double> proj(dim);
+    for (uint32_t j = 0; j < dim; ++j) {
+        double* aj = &g[(size_t)j * dim];
+        for (int pass = 0; pass < 2; ++pass) {
+            auto dots = [&](uint32_t lo, uint32_t hi) {
+                for (uint32_t i = lo; i < hi; ++i) {
+                    const double* qi = &g[(size_t)i * dim];
+                    double s = 0.0;
+                    for (uint32_t k = 0; k < dim; ++k) s += qi[k] * aj[k];
+                    proj[i] = s;
+                }
+            };
+            if (threads > 1 && j >= 256) {
+                std::vector<std::thread> th;
+                for (unsigned t = 0; t < threads; ++t)
+                    th.emplace_back(dots, (uint32_t)((uint64_t)j * t / threads), (uint32_t)((uint64_t)j * (t + 1) / threads));
+                for (auto& x : th) x.join();
+            } else {
+                dots(0, j);
+            }
+            for (uint32_t i = 0; i < j; ++i) {
+                const double* qi = &g[(size_t)i * dim];
+                const double p = proj[i];
+                for (uint32_t k = 0; k < dim; ++k) aj[k] -= p * qi[k];
+            }
+        }
+        double nrm = 0.0;
+        for (uint32_t k = 0; k < dim; ++k) nrm += aj[k] * aj[k];
+        nrm = std::sqrt(nrm);
+        for (uint32_t k = 0; k < dim; ++k) aj[k] /= nrm;
+    }
+}
+
+void make_transform(uint32_t d, uint64_t seed, std::vector<float>& rot) {
+    Rng rng(seed, 1);
+    std::vector<double> g((size_t)d * d);
+    for (auto& x : g) x = rng.normal();
+    unsigned threads = std::max(1u, std::min(8u, std::thread::hardware_concurrency()));
+    orthonormalise(g, d, threads);
+    rot.resize((size_t)d * d);
+    // orthonormal columns are as good as rows: rot[j][k] = column j, element k
+    for (size_t i = 0; i < rot.size(); ++i) rot[i] = (float)g[i];
+}
+
+// cb[l][j][k]: per subspace, cross-polytopes rotated independently; from each polytope its axes in
+// order, first with sign +, then with sign -, until 16 vectors are collected; norm 1/sqrt(P).
+void make_codebooks(uint32_t d, uint32_t P, uint64_t seed, std::vector<float>& cb) {
+    const uint32_t ds = d / P;
+    Rng rng(seed, 2);
+    cb.assign((size_t)P * PAG_NCODE * ds, 0.f);
+    const double scale = 1.0 / std::sqrt((double)P);
+    std::vector<double> g((size_t)ds * ds);
+    for (uint32_t l = 0; l < P; ++l) {
+        uint32_t j = 0;
+        while (j < PAG_NCODE) {
+            for (auto& x : g) x = rng.normal();
+            orthonormalise(g, ds, 1);
+            const uint32_t k = std::min<uint32_t>(ds, (PAG_NCODE - j) / 2);
+            for (uint32_t a = 0; a < k; ++a)
+                for (uint32_t e = 0; e < ds; ++e) {
+                    const double v = g[(size_t)a * ds + e] * scale;
+                    cb[((size_t)l * PAG_NCODE + j + a) * ds + e] = (float)v;
+                    cb[((size_t)l * PAG_NCODE + j + k + a) * ds + e] = (float)(-v);
+                }
+            j += 2 * k;
+        }
+    }
+}
+
+int make_layout(uint32_t d, uint32_t P, uint32_t deg, pag_layout* L) {
+    PAG_CHECK(d > 0 && P > 0 && deg > 0, PAG_EINVAL, "d, num_subspaces and max_degree must be positive");
+    PAG_CHECK(d % P == 0, PAG_EINVAL, "d must be divisible by num_subspaces");
+    PAG_CHECK(d % 4 == 0 && d <= 3072, PAG_EUNSUPPORTED, "this build needs d % 4 == 0 and d <= 3072");
+    PAG_CHECK(P <= 8 * PAG_MAX_CW, PAG_EUNSUPPORTED, "this build needs num_subspaces <= 64");
+    PAG_CHECK(deg <= PAG_MAX_DEG, PAG_EUNSUPPORTED, "this build needs max_degree <= 64");
+    L->d = d; L->P = P; L->dsub = d / P; L->deg = deg;
+    L->Ppad = (P + 15) / 16 * 16;
+    L->cw = L->Ppad / 8;
+    L->off_a = deg * 4;
+    L->off_c = deg * 8;
+    L->off_codes = deg * 12;
+    L->rec_bytes = (deg * 12 + deg * L->cw * 4 + 127) / 128 * 128;
+    return PAG_OK;
+}
+
+int check_params(const pag_params* p) {
+    PAG_CHECK(p != nullptr, PAG_EINVAL, "params is null");
+    PAG_CHECK(p->struct_size == sizeof(pag_params), PAG_EINVAL, "pag_params.struct_size does not match this library");
+    PAG_CHECK(p->metric >= PAG_L2 && p->metric <= PAG_COS, PAG_EINVAL, "unknown metric");
+    PAG_CHECK(p->ef_construction >= 1, PAG_EINVAL, "ef_construction must be >= 1");
+    PAG_CHECK(p->search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 128 is not built");
+    return PAG_OK;
+}
+
+template <typename T>
+int dev_alloc(T** p, u64 count) {
+    *p = nullptr;
+    if (count == 0) count = 1;
+    hipError_t e = hipMalloc((void**)p, count * sizeof(T));
+    if (e != hipSuccess) { pag_set_error(std::string("hipMalloc: ") + hipGetErrorString(e)); return PAG_ENOMEM; }
+    return PAG_OK;
+}
+
+template <typename T>
+int ensure_ws(T** p, u64* cap, u64 need) {
+    if (*cap >= need) return PAG_OK;
+    if (*p) { hipError_t e = hipFree(*p); (void)e; *p = nullptr; *cap = 0; }
+    int rc = dev_alloc(p, need);
+    if (rc == PAG_OK) *cap = need;
+    return rc;
+}
+
+struct DeviceGuard {
+    int prev = -1;
+    explicit DeviceGuard(int dev) { if (hipGetDevice(&prev) != hipSuccess) prev = -1; if (prev != dev) (void)hipSetDevice(dev); else prev = -1; }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+// allocate the HBM-resident parts of an index for `capacity` nodes
+int alloc_index(pag_index* ix) {
+    int rc;
+    if ((rc = dev_alloc(&ix->vec, ix->capacity * ix->L.d))) return rc;
+    if ((rc = dev_alloc(&ix->rec, ix->capacity * ix->L.rec_bytes))) return rc;
+    if ((rc = dev_alloc(&ix->e2, ix->capacity * ix->L.deg))) return rc;
+    if ((rc = dev_alloc(&ix->rot, (u64)ix->L.d * ix->L.d))) return rc;
+    if ((rc = dev_alloc(&ix->cb, (u64)ix->L.P * PAG_NCODE * ix->L.dsub))) return rc;
+    if ((rc = dev_alloc(&ix->entry, 1024))) return rc;
+    if ((rc = dev_alloc(&ix->d_qcounter, 4))) return rc;
+    if ((rc = dev_alloc(&ix->d_counters, CTR_COUNT))) return rc;
+    PAG_HIP(hipMemsetAsync(ix->d_counters, 0, CTR_COUNT * sizeof(u64), ix->stream));
+    for (auto& e : ix->ev) PAG_HIP(hipEventCreate(&e));
+    return PAG_OK;
+}
+
+pag_index* new_index(const pag_params* p, uint32_t d) {
+    pag_index* ix = new pag_index();
+    std::memset((void*)ix, 0, sizeof(*ix));
+    (void)hipGetDevice(&ix->device);
+    ix->stream = (hipStream_t)p->stream;
+    ix->metric = p->metric;
+    ix->efC = p->ef_construction;
+    ix->search_b = p->search_b;
+    ix->subbatch = p->insert_subbatch;
+    ix->flags = p->flags;
+    ix->seed = p->seed;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, ix->device) == hipSuccess) ix->num_cu = prop.multiProcessorCount;
+    if (ix->num_cu <= 0) ix->num_cu = 256;
+    (void)d;
+    return ix;
+}
+
+int set_entry_list(pag_index* ix) {
+    const u32 ne = (u32)std::min<u64>(ix->n, 1024);
+    std::vector<u32> e(ne ? ne : 1);
+    for (u32 i = 0; i < ne; ++i) e[i] = i;
+    PAG_HIP(hipMemcpyAsync(ix->entry, e.data(), ne * sizeof(u32), hipMemcpyHostToDevice, ix->stream));
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    ix->n_entry = ne;
+    return PAG_OK;
+}
+
+// normalise (COS) + rotate `rows` raw vectors X (dev) into dst (dev)
+int ingest(pag_index* ix, const float* X, u64 rows, float* dst) {
+    const float* src = X;
+    int rc;
+    if (ix->metric == PAG_COS) {
+        if ((rc = ensure_ws(&ix->ws_norm, &ix->ws_norm_cap, rows * ix->L.d))) return rc;
+        if ((rc = pag_launch_normalise(ix->stream, X, rows, ix->L.d, ix->ws_norm))) return rc;
+        src = ix->ws_norm;
+    }
+    return pag_launch_rotate(ix->stream, src, rows, ix->L.d, ix->rot, dst);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+
+extern "C" int pag_free(pag_index* ix) {
+    if (!ix) return PAG_OK;
+    DeviceGuard g(ix->device);
+    (void)hipStreamSynchronize(ix->stream);
+    void* ptrs[] = { ix->vec, ix->rec, ix->e2, ix->rot, ix->cb, ix->entry, ix->ws_qrot, ix->ws_tab, ix->ws_norm,
+                     ix->ws_bitmap, ix->d_qcounter, ix->d_counters };
+    for (void* p : ptrs) if (p) (void)hipFree(p);
+    for (auto& e : ix->ev) if (e) (void)hipEventDestroy(e);
+    delete ix;
+    return PAG_OK;
+}
+
+extern "C" int pag_build(const float* D, uint64_t n, uint32_t d, const pag_params* params, pag_index** out) {
+    PAG_CHECK(out != nullptr, PAG_EINVAL, "out is null");
+    *out = nullptr;
+    int rc = check_params(params);
+    if (rc) return rc;
+    PAG_CHECK(D != nullptr && n > 0, PAG_EINVAL, "D is null or n == 0");
+    PAG_CHECK(n < (1ull << 31), PAG_EUNSUPPORTED, "n must be below 2^31");
+    pag_layout L;
+    if ((rc = make_layout(d, params->num_subspaces, params->max_degree, &L))) return rc;
+    const u32 b_idx = std::min<u32>(params->ef_construction, 100);
+    (void)b_idx;
+    pag_index* ix = new_index(params, d);
+    ix->L = L;
+    ix->capacity = std::max<u64>(params->capacity, n);
+    if (ix->capacity >= (1ull << 31)) { pag_free(ix); pag_set_error("capacity must be below 2^31"); return PAG_EUNSUPPORTED; }
+    const auto t0 = std::chrono::steady_clock::now();
+    if ((rc = alloc_index(ix))) { pag_free(ix); return rc; }
+    std::vector<float> rot, cb;
+    make_transform(d, params->seed, rot);
+    make_codebooks(d, L.P, params->seed, cb);
+    hipError_t e = hipMemcpyAsync(ix->rot, rot.data(), rot.size() * 4, hipMemcpyHostToDevice, ix->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(ix->cb, cb.data(), cb.size() * 4, hipMemcpyHostToDevice, ix->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(ix->rec, 0xFF, ix->capacity * L.rec_bytes, ix->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ix->stream);
+    if (e != hipSuccess) { pag_free(ix); pag_set_error(std::string("pag_build upload: ") + hipGetErrorString(e)); return PAG_EHIP; }
+    if ((rc = ingest(ix, D, n, ix->vec))) { pag_free(ix); return rc; }
+    ix->n = 0;
+    if ((rc = pag_build_range(ix, 0, n))) { pag_free(ix); return rc; }
+    ix->n = n;
+    if ((rc = set_entry_list(ix))) { pag_free(ix); return rc; }
+    ix->last_build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    *out = ix;
+    return PAG_OK;
+}
+
+extern "C" int pag_insert(pag_index* ix, const float* X, uint64_t m) {
+    PAG_CHECK(ix != nullptr, PAG_EINVAL, "index is null");
+    if (m == 0) return PAG_OK;
+    PAG_CHECK(X != nullptr, PAG_EINVAL, "X is null");
+    PAG_CHECK(ix->n + m <= ix->capacity, PAG_ECAPACITY, "pag_insert: capacity exceeded");
+    DeviceGuard g(ix->device);
+    const auto t0 = std::chrono::steady_clock::now();
+    int rc;
+    if ((rc = ingest(ix, X, m, ix->vec + ix->n * ix->L.d))) return rc;
+    if ((rc = pag_build_range(ix, ix->n, ix->n + m))) return rc;
+    ix->n += m;
+    if ((rc = set_entry_list(ix))) return rc;
+    ix->last_build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return PAG_OK;
+}
+
+extern "C" int pag_describe(const pag_index* ix, pag_arrays* out) {
+    PAG_CHECK(ix && out, PAG_EINVAL, "null argument");
+    PAG_CHECK(out->struct_size == sizeof(pag_arrays), PAG_EINVAL, "pag_arrays.struct_size does not match this library");
+    out->metric = ix->metric; out->n = ix->n; out->d = ix->L.d; out->num_subspaces = ix->L.P;
+    out->max_degree = ix->L.deg; out->n_entry = ix->n_entry;
+    return PAG_OK;
+}
+
+extern "C" int pag_export(const pag_index* ix, pag_arrays* out) {
+    PAG_CHECK(ix && out, PAG_EINVAL, "null argument");
+    PAG_CHECK(out->struct_size == sizeof(pag_arrays), PAG_EINVAL, "pag_arrays.struct_size does not match this library");
+    PAG_CHECK(out->vectors && out->adj && out->a && out->c && out->e2 && out->codes && out->rotation &&
+              out->codebooks && out->entry, PAG_EINVAL, "pag_export: every output array must be allocated");
+    DeviceGuard g(ix->device);
+    const pag_layout& L = ix->L;
+    const u64 n = ix->n;
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    PAG_HIP(hipMemcpy(out->vectors, ix->vec, n * L.d * 4, hipMemcpyDeviceToHost));
+    PAG_HIP(hipMemcpy(out->e2, ix->e2, n * L.deg * 4, hipMemcpyDeviceToHost));
+    PAG_HIP(hipMemcpy(out->rotation, ix->rot, (u64)L.d * L.d * 4, hipMemcpyDeviceToHost));
+    PAG_HIP(hipMemcpy(out->codebooks, ix->cb, (u64)L.P * PAG_NCODE * L.dsub * 4, hipMemcpyDeviceToHost));
+    PAG_HIP(hipMemcpy(out->entry, ix->entry, ix->n_entry * 4, hipMemcpyDeviceToHost));
+    const u64 slab = 1 << 16;
+    std::vector<uint8_t> buf(std::min<u64>(slab, std::max<u64>(n, 1)) * L.rec_bytes);
+    for (u64 s = 0; s < n; s += slab) {
+        const u64 cnt = std::min<u64>(slab, n - s);
+        PAG_HIP(hipMemcpy(buf.data(), ix->rec + s * L.rec_bytes, cnt * L.rec_bytes, hipMemcpyDeviceToHost));
+        for (u64 i = 0; i < cnt; ++i) {
+            const uint8_t* rec = buf.data() + i * L.rec_bytes;
+            const u64 o = (s + i) * L.deg;
+            std::memcpy(out->adj + o, rec, L.deg * 4);
+            std::memcpy(out->a + o, rec + L.off_a, L.deg * 4);
+            std::memcpy(out->c + o, rec + L.off_c, L.deg * 4);
+            const u32* cw = (const u32*)(rec + L.off_codes);
+            for (u32 e = 0; e < L.deg; ++e)
+                for (u32 l = 0; l < L.P; ++l)
+                    out->codes[(o + e) * L.P + l] = (uint8_t)((cw[e * L.cw + l / 8] >> (4 * (l % 8))) & 15u);
+        }
+    }
+    out->metric = ix->metric; out->n = n; out->d = L.d; out->num_subspaces = L.P; out->max_degree = L.deg;
+    out->n_entry = ix->n_entry;
+    return PAG_OK;
+}
+
+extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_index** out) {
+    PAG_CHECK(out != nullptr, PAG_EINVAL, "out is null");
+    *out = nullptr;
+    int rc = check_params(params);
+    if (rc) return rc;
+    PAG_CHECK(in != nullptr && in->struct_size == sizeof(pag_arrays), PAG_EINVAL, "pag_arrays is null or of another size");
+    PAG_CHECK(in->vectors && in->adj && in->a && in->c && in->e2 && in->codes && in->rotation && in->codebooks &&
+              in->entry, PAG_EINVAL, "pag_import: every array is required");
+    PAG_CHECK(in->n > 0 && in->n < (1ull << 31), PAG_EINVAL, "pag_import: n out of range");
+    PAG_CHECK(in->n_entry >= 1 && in->n_entry <= 1024, PAG_EINVAL, "pag_import: n_entry must be in 1..1024");
+    PAG_CHECK(in->metric >= PAG_L2 && in->metric <= PAG_COS, PAG_EINVAL, "pag_import: unknown metric");
+    pag_layout L;
+    if ((rc = make_layout(in->d, in->num_subspaces, in->max_degree, &L))) return rc;
+    const u64 n = in->n;
+    for (u64 i = 0; i < n * L.deg; ++i)
+        PAG_CHECK(in->adj[i] == PAG_EMPTY || in->adj[i] < n, PAG_EINVAL, "pag_import: neighbour id out of range");
+    for (u32 i = 0; i < in->n_entry; ++i) PAG_CHECK(in->entry[i] < n, PAG_EINVAL, "pag_import: entry id out of range");
+    for (u64 i = 0; i < n * L.deg * L.P; ++i) PAG_CHECK(in->codes[i] < PAG_NCODE, PAG_EINVAL, "pag_import: code above 15");
+    pag_index* ix = new_index(params, in->d);
+    ix->metric = in->metric;
+    ix->L = L;
+    ix->capacity = std::max<u64>(params->capacity, n);
+    if ((rc = alloc_index(ix))) { pag_free(ix); return rc; }
+    auto fail = [&](hipError_t e) { pag_set_error(std::string("pag_import: ") + hipGetErrorString(e)); pag_free(ix); return PAG_EHIP; };
+    hipError_t e;
+    if ((e = hipMemsetAsync(ix->rec, 0xFF, ix->capacity * L.rec_bytes, ix->stream)) != hipSuccess) return fail(e);
+    if ((e = hipStreamSynchronize(ix->stream)) != hipSuccess) return fail(e);
+    if ((e = hipMemcpy(ix->vec, in->vectors, n * L.d * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+    if ((e = hipMemcpy(ix->e2, in->e2, n * L.deg * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+    if ((e = hipMemcpy(ix->rot, in->rotation, (u64)L.d * L.d * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+    if ((e = hipMemcpy(ix->cb, in->codebooks, (u64)L.P * PAG_NCODE * L.dsub * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+    if ((e = hipMemcpy(ix->entry, in->entry, in->n_entry * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+    ix->n_entry = in->n_entry;
+    const u64 slab = 1 << 16;
+    std::vector<uint8_t> buf(std::min<u64>(slab, n) * L.rec_bytes);
+    for (u64 s = 0; s < n; s += slab) {
+        const u64 cnt = std::min<u64>(slab, n - s);
+        std::memset(buf.data(), 0, cnt * L.rec_bytes);
+        for (u64 i = 0; i < cnt; ++i) {
+            uint8_t* rec = buf.data() + i * L.rec_bytes;
+            const u64 o = (s + i) * L.deg;
+            std::memcpy(rec, in->adj + o, L.deg * 4);
+            std::memcpy(rec + L.off_a, in->a + o, L.deg * 4);
+            std::memcpy(rec + L.off_c, in->c + o, L.deg * 4);
+            u32* cw = (u32*)(rec + L.off_codes);
+            for (u32 ed = 0; ed < L.deg; ++ed)
+                for (u32 l = 0; l < L.P; ++l)
+                    cw[ed * L.cw + l / 8] |= (u32)(in->codes[(o + ed) * L.P + l] & 15u) << (4 * (l % 8));
+        }
+        if ((e = hipMemcpy(ix->rec + s * L.rec_bytes, buf.data(), cnt * L.rec_bytes, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+    }
+    ix->n = n;
+    *out = ix;
+    return PAG_OK;
+}
+
+extern "C" int pag_get_counters(const pag_index* ix, pag_counters* out) {
+    PAG_CHECK(ix && out, PAG_EINVAL, "null argument");
+    PAG_CHECK(out->struct_size == sizeof(pag_counters), PAG_EINVAL, "pag_counters.struct_size does not match this library");
+    DeviceGuard g(ix->device);
+    u64 h[CTR_COUNT];
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    PAG_HIP(hipMemcpy(h, ix->d_counters, sizeof h, hipMemcpyDeviceToHost));
+    out->adj_record_bytes = ix->L.rec_bytes;
+    out->queries = h[CTR_QUERIES]; out->hops = h[CTR_HOPS]; out->tests = h[CTR_TESTS]; out->passes = h[CTR_PASSES];
+    out->exact = h[CTR_EXACT]; out->rounds = h[CTR_ROUNDS]; out->rf_overflow = h[CTR_RF_OVER];
+    out->rt_overflow = h[CTR_RT_OVER]; out->seen_spills = h[CTR_SPILLS];
+    out->last_search_kernel_ms = ix->last_search_ms;
+    out->last_prepare_ms = ix->last_prepare_ms;
+    out->last_build_ms = ix->last_build_ms;
+    return PAG_OK;
+}
+
+extern "C" int pag_reset_counters(pag_index* ix) {
+    PAG_CHECK(ix, PAG_EINVAL, "null argument");
+    DeviceGuard g(ix->device);
+    int rc = pag_launch_zero_u32(ix->stream, (u32*)ix->d_counters, CTR_COUNT * 2);
+    if (rc) return rc;
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    return PAG_OK;
+}
+
+extern "C" int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t flags) {
+    PAG_CHECK(ix, PAG_EINVAL, "null argument");
+    PAG_CHECK(search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 128 is not built");
+    ix->search_b = search_b;
+    ix->flags = flags;
+    return PAG_OK;
+}
+
+extern "C" int pag_set_seen_capacity_log2(pag_index* ix, uint32_t log2_slots) {
+    PAG_CHECK(ix, PAG_EINVAL, "null argument");
+    PAG_CHECK(log2_slots == 0 || (log2_slots >= 6 && log2_slots <= 13), PAG_EINVAL, "seen capacity log2 must be 0 or in 6..13");
+    ix->seen_log2 = log2_slots;
+    return PAG_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// search
+// ---------------------------------------------------------------------------------------------
+
+static int prepare(pag_index* ix, const float* Q, u64 nq, float* qrot, float* tables) {
+    const float* src = Q;
+    int rc;
+    if (ix->metric == PAG_COS) {
+        if ((rc = ensure_ws(&ix->ws_norm, &ix->ws_norm_cap, nq * ix->L.d))) return rc;
+        if ((rc = pag_launch_normalise(ix->stream, Q, nq, ix->L.d, ix->ws_norm))) return rc;
+        src = ix->ws_norm;
+    }
+    if ((rc = pag_launch_rotate(ix->stream, src, nq, ix->L.d, ix->rot, qrot))) return rc;
+    return pag_launch_tables(ix->stream, qrot, nq, ix->L, ix->cb, tables);
+}
+
+static u32 seen_log2_for(const pag_index* ix, u32 ef, u32 b) {
+    if (ix->seen_log2) return ix->seen_log2;
+    // room for about twice the exact distances of a typical search (entries + a few per visited node)
+    const u32 want = 2 * (b + 8 * std::max(ef, b));
+    u32 lg = 10;
+    while ((1u << lg) < want && lg < 13) ++lg;
+    return lg;
+}
+
+// Fills the part of SearchArgs that depends only on the index and (b, ef); shared with indexing.
+int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid) {
+    const pag_layout& L = ix->L;
+    std::memset((void*)a, 0, sizeof(*a));
+    a->vec = ix->vec; a->rec = ix->rec; a->entry = ix->entry;
+    a->n_entry = (u32)std::min<u64>(ix->n_entry, n_limit);
+    a->n_limit = (u32)n_limit;
+    a->d = L.d; a->deg = L.deg; a->Ppad = L.Ppad; a->cw = L.cw; a->rec_bytes = L.rec_bytes;
+    a->off_a = L.off_a; a->off_c = L.off_c; a->off_codes = L.off_codes;
+    a->b = b; a->Rmax = std::max<u32>(1, (ef + b - 1) / b);
+    a->hlog = seen_log2_for(ix, ef, b);
+    a->flags = ix->flags;
+    a->qcounter = ix->d_qcounter; a->counters = ix->d_counters;
+    *lds = (u32)pag_search_lds_bytes(L, b, a->hlog, a);
+    int rc = pag_search_max_grid(ix, b, *lds, grid);
+    if (rc) return rc;
+    // per-wave spill bitmaps of the seen set: one bit per node, rounded to 16 bytes
+    a->bitmap_words = ((u64)ix->capacity + 127) / 128 * 4;
+    const u64 need = (u64)*grid * a->bitmap_words;
+    if (ix->ws_bitmap_cap < need) {
+        // a fresh buffer starts dirty: clear it once; every wave leaves its slice clean afterwards
+        if ((rc = ensure_ws(&ix->ws_bitmap, &ix->ws_bitmap_cap, need))) return rc;
+        PAG_HIP(hipMemsetAsync(ix->ws_bitmap, 0, need * 4, ix->stream));
+    }
+    a->bitmap = ix->ws_bitmap;
+    return PAG_OK;
+}
+
+extern "C" int pag_search(const pag_index* cix, const float* Q, uint64_t nq, uint32_t K, uint32_t efS,
+                          int64_t* ids, float* dists) {
+    pag_index* ix = const_cast<pag_index*>(cix);   // workspaces and counters are mutable state of the handle
+    PAG_CHECK(ix != nullptr, PAG_EINVAL, "index is null");
+    if (nq == 0) return PAG_OK;
+    PAG_CHECK(Q && ids && dists, PAG_EINVAL, "Q, ids or dists is null");
+    PAG_CHECK(K >= 1 && K <= ix->n, PAG_EINVAL, "K must be in 1..n");
+    PAG_CHECK(efS >= 1, PAG_EINVAL, "efS must be >= 1");
+    PAG_CHECK(nq < (1ull << 31), PAG_EINVAL, "nq must be below 2^31");
+    const u32 b = ix->search_b ? ix->search_b : std::max<u32>(10, K);
+    PAG_CHECK(b >= K, PAG_EINVAL, "search_b must be >= K");
+    PAG_CHECK(b <= PAG_MAX_B, PAG_EUNSUPPORTED, "working sets above 128 nodes (K > 128) are not built");
+    DeviceGuard g(ix->device);
+    const pag_layout& L = ix->L;
+    int rc;
+    if ((rc = ensure_ws(&ix->ws_qrot, &ix->ws_qrot_cap, nq * L.d))) return rc;
+    if ((rc = ensure_ws(&ix->ws_tab, &ix->ws_tab_cap, nq * L.Ppad * PAG_NCODE))) return rc;
+    SearchArgs a;
+    u32 lds = 0;
+    int grid = 0;
+    if ((rc = pag_search_common(ix, b, efS, ix->n, &a, &lds, &grid))) return rc;
+    a.qrot = ix->ws_qrot; a.tables = ix->ws_tab;
+    a.nq = (u32)nq; a.K = K;
+    a.out_ids = (long long*)ids; a.out_dists = dists;
+    a.out_scale = ix->metric == PAG_L2 ? 1.0f : 0.5f;
+    PAG_HIP(hipEventRecord(ix->ev[0], ix->stream));
+    if ((rc = prepare(ix, Q, nq, ix->ws_qrot, ix->ws_tab))) return rc;
+    if ((rc = pag_launch_zero_u32(ix->stream, ix->d_qcounter, 1))) return rc;
+    PAG_HIP(hipEventRecord(ix->ev[1], ix->stream));
+    if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
+    PAG_HIP(hipEventRecord(ix->ev[2], ix->stream));
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    float ms = 0.f;
+    PAG_HIP(hipEventElapsedTime(&ms, ix->ev[0], ix->ev[1])); ix->last_prepare_ms = ms;
+    PAG_HIP(hipEventElapsedTime(&ms, ix->ev[1], ix->ev[2])); ix->last_search_ms = ms;
+    return PAG_OK;
+}
+
+extern "C" int pag_prepare_queries(const pag_index* cix, const float* Q, uint64_t nq, float* q_rot, float* tables) {
+    pag_index* ix = const_cast<pag_index*>(cix);
+    PAG_CHECK(ix && Q && q_rot && tables, PAG_EINVAL, "null argument");
+    DeviceGuard g(ix->device);
+    const pag_layout& L = ix->L;
+    int rc;
+    // the search keeps zero-padded tables of Ppad rows; this entry point returns the P real rows
+    if ((rc = ensure_ws(&ix->ws_tab, &ix->ws_tab_cap, nq * L.Ppad * PAG_NCODE))) return rc;
+    if ((rc = prepare(ix, Q, nq, q_rot, ix->ws_tab))) return rc;
+    PAG_HIP(hipMemcpy2DAsync(tables, (size_t)L.P * PAG_NCODE * 4, ix->ws_tab, (size_t)L.Ppad * PAG_NCODE * 4,
+                             (size_t)L.P * PAG_NCODE * 4, nq, hipMemcpyDeviceToDevice, ix->stream));
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    return PAG_OK;
+}
+
+extern "C" int pag_exact_distances(const pag_index* ix, const float* q_rot, uint64_t nq, const uint32_t* ids,
+                                   uint32_t m, float* keys) {
+    PAG_CHECK(ix && q_rot && ids && keys, PAG_EINVAL, "null argument");
+    DeviceGuard g(ix->device);
+    int rc = pag_launch_exact(ix->stream, ix, q_rot, nq, ids, m, keys);
+    if (rc) return rc;
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    return PAG_OK;
+}
+
+extern "C" int pag_screen(const pag_index* cix, const float* tables, uint64_t nq, const uint32_t* u,
+                          const float* Du, float* est) {
+    pag_index* ix = const_cast<pag_index*>(cix);
+    PAG_CHECK(ix && tables && u && Du && est, PAG_EINVAL, "null argument");
+    DeviceGuard g(ix->device);
+    const pag_layout& L = ix->L;
+    int rc;
+    // widen the caller's [P][16] tables to the zero-padded [Ppad][16] form the kernels read
+    if ((rc = ensure_ws(&ix->ws_tab, &ix->ws_tab_cap, nq * L.Ppad * PAG_NCODE))) return rc;
+    PAG_HIP(hipMemsetAsync(ix->ws_tab, 0, nq * L.Ppad * PAG_NCODE * 4, ix->stream));
+    PAG_HIP(hipMemcpy2DAsync(ix->ws_tab, (size_t)L.Ppad * PAG_NCODE * 4, tables, (size_t)L.P * PAG_NCODE * 4,
+                             (size_t)L.P * PAG_NCODE * 4, nq, hipMemcpyDeviceToDevice, ix->stream));
+    if ((rc = pag_launch_screen(ix->stream, ix, ix->ws_tab, nq, u, Du, est))) return rc;
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    return PAG_OK;
+}
+
+extern "C" int pag_edge_info(const pag_index* cix, uint64_t node_begin, uint64_t node_end, uint8_t* codes,
+                             float* a, float* c, float* e2) {
+    pag_index* ix = const_cast<pag_index*>(cix);
+    PAG_CHECK(ix && codes && a && c && e2, PAG_EINVAL, "null argument");
+    PAG_CHECK(node_begin <= node_end && node_end <= ix->n, PAG_EINVAL, "node range out of bounds");
+    if (node_begin == node_end) return PAG_OK;
+    DeviceGuard g(ix->device);
+    const pag_layout& L = ix->L;
+    const u64 m = node_end - node_begin;
+    // work on a scratch copy of the records so that the index itself is left untouched
+    pag_index tmp = *ix;
+    int rc;
+    if ((rc = dev_alloc(&tmp.rec, m * L.rec_bytes))) return rc;
+    if ((rc = dev_alloc(&tmp.e2, m * L.deg))) { (void)hipFree(tmp.rec); return rc; }
+    std::vector<uint8_t> buf(m * L.rec_bytes);
+    std::vector<float> he2(m * L.deg);
+    hipError_t e = hipMemcpyAsync(tmp.rec, ix->rec + node_begin * L.rec_bytes, m * L.rec_bytes, hipMemcpyDeviceToDevice, ix->stream);
+    // the kernel addresses records and e2 by absolute node id: shift the bases
+    tmp.rec -= node_begin * L.rec_bytes;
+    tmp.e2 -= node_begin * L.deg;
+    if (e == hipSuccess) rc = pag_launch_edge_info_nodes(ix->stream, &tmp, node_begin, node_end);
+    tmp.rec += node_begin * L.rec_bytes;
+    tmp.e2 += node_begin * L.deg;
+    if (e == hipSuccess && rc == PAG_OK) e = hipStreamSynchronize(ix->stream);
+    if (e == hipSuccess && rc == PAG_OK) e = hipMemcpy(buf.data(), tmp.rec, buf.size(), hipMemcpyDeviceToHost);
+    if (e == hipSuccess && rc == PAG_OK) e = hipMemcpy(he2.data(), tmp.e2, he2.size() * 4, hipMemcpyDeviceToHost);
+    (void)hipFree(tmp.rec); (void)hipFree(tmp.e2);
+    if (rc) return rc;
+    if (e != hipSuccess) { pag_set_error(std::string("pag_edge_info: ") + hipGetErrorString(e)); return PAG_EHIP; }
+    for (u64 i = 0; i < m; ++i) {
+        const uint8_t* rec = buf.data() + i * L.rec_bytes;
+        std::memcpy(a + i * L.deg, rec + L.off_a, L.deg * 4);
+        std::memcpy(c + i * L.deg, rec + L.off_c, L.deg * 4);
+        std::memcpy(e2 + i * L.deg, he2.data() + i * L.deg, L.deg * 4);
+        const u32* cw = (const u32*)(rec + L.off_codes);
+        for (u32 ed = 0; ed < L.deg; ++ed)
+            for (u32 l = 0; l < L.P; ++l)
+                codes[(i * L.deg + ed) * L.P + l] = (uint8_t)((cw[ed * L.cw + l / 8] >> (4 * (l % 8))) & 15u);
+    }
+    return PAG_OK;
+}

@@ -1,0 +1,343 @@
+// Batch-synchronous index construction and online insertion (Alg. 1, Step 1; Sec. 4.1).
+//
+// The paper inserts nodes one after another.  Here a batch of new nodes searches the graph built
+// so far concurrently (the same PRT-TFB search kernel as for queries, with ef = efC,
+// b = min(efC, 100) and R_L collecting every round's W), then
+//   1. RobustPrune (Eq. 1, alpha = 1) over each node's R_L gives N_out(v);
+//   2. the reverse edges (u <- v for u in N_out(v)) are grouped by target with a radix sort and
+//      one wave per target applies them in ascending (distance, id) order;
+//   3. the inference information (codes, a, c) of every new or moved edge is recomputed.
+// Batches start small and grow with the graph so that early nodes see most of their peers.
+#include <hipcub/hipcub.hpp>
+
+#include <algorithm>
+#include <vector>
+
+#include "pag_internal.h"
+
+int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid);
+
+namespace {
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// squared distance between the vector staged in LDS and row `id`, all lanes get the result
+__device__ __forceinline__ float dist_lds(const float* __restrict__ vec, u32 d, const float* s, u32 id, int lane) {
+    const float4* x = (const float4*)(vec + (u64)id * d);
+    const float4* q = (const float4*)s;
+    double acc = 0.0;
+    for (u32 c = lane; c < d / 4; c += 64) {
+        const float4 a = q[c], b = x[c];
+        const float dx = a.x - b.x, dy = a.y - b.y, dz = a.z - b.z, dw = a.w - b.w;
+        acc = __builtin_fma((double)dx, (double)dx, acc);
+        acc = __builtin_fma((double)dy, (double)dy, acc);
+        acc = __builtin_fma((double)dz, (double)dz, acc);
+        acc = __builtin_fma((double)dw, (double)dw, acc);
+    }
+    return (float)wave_sum(acc);
+}
+
+__device__ __forceinline__ void stage(const float* __restrict__ vec, u32 d, u32 id, float* s, int lane) {
+    const float4* x = (const float4*)(vec + (u64)id * d);
+    for (u32 c = lane; c < d / 4; c += 64) ((float4*)s)[c] = x[c];
+}
+
+// ---- initial nodes: each of the first n_init nodes is linked to its nearest min(deg, n_init-1) peers ----
+__global__ void __launch_bounds__(64) k_init_clique(const float* __restrict__ vec, uint8_t* __restrict__ recs,
+                                                    pag_layout L, u32 n_init) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sv = (float*)smem;                       // [d]
+    u64* keys = (u64*)(sv + L.d);                   // [n_init]
+    u64* sorted = keys + n_init;                    // [n_init]
+    const u32 v = blockIdx.x;
+    const int lane = threadIdx.x;
+    stage(vec, L.d, v, sv, lane);
+    __syncthreads();
+    for (u32 o = 0; o < n_init; ++o) {
+        const float dist = dist_lds(vec, L.d, sv, o, lane);
+        if (lane == 0) keys[o] = o == v ? PAG_KEY_INVALID : (((u64)__float_as_uint(dist) << 32) | o);
+    }
+    __syncthreads();
+    for (u32 i = lane; i < n_init; i += 64) {
+        const u64 k = keys[i];
+        u32 r = 0;
+        for (u32 j = 0; j < n_init; ++j) r += (keys[j] < k || (keys[j] == k && j < i)) ? 1u : 0u;
+        sorted[r] = k;
+    }
+    __syncthreads();
+    u32* ids = (u32*)(recs + (u64)v * L.rec_bytes);
+    const u32 take = n_init - 1 < L.deg ? n_init - 1 : L.deg;
+    if ((u32)lane < L.deg) ids[lane] = (u32)lane < take ? (u32)(sorted[lane] & 0xFFFFFFFFull) : PAG_EMPTY;
+}
+
+// ---- RobustPrune over R_L of each new node (Eq. 1, alpha = 1) ----
+// cand: per node the keys collected by the search (dist bits << 32 | id << 1 | visited), unsorted
+// across rounds.  Sorted ascending, cut to efC, then scanned: a candidate is kept unless an
+// already kept s has ||s - c|| <= ||v - c||.  Writes N_out(v) into v's record and one reverse
+// pair per kept neighbour: key = target << 32 | dist bits, value = v.
+__global__ void __launch_bounds__(64) k_prune_new(const float* __restrict__ vec, uint8_t* __restrict__ recs,
+                                                  pag_layout L, u32 node0, u32 m, const u64* __restrict__ cand,
+                                                  const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
+                                                  u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sv = (float*)smem;                  // [d] candidate vector
+    u64* sorted = (u64*)(sv + L.d);            // [cand_cap]
+    u32* kept = (u32*)(sorted + cand_cap);     // [deg]
+    const u32 vi = blockIdx.x;
+    if (vi >= m) return;
+    const int lane = threadIdx.x;
+    const u32 v = node0 + vi;
+    const u64* mine = cand + (u64)vi * cand_cap;
+    u32 nc = cand_cnt[vi];
+    if (nc > cand_cap) nc = cand_cap;
+    for (u32 i = lane; i < nc; i += 64) {
+        const u64 k = mine[i] & ~1ull;           // drop the visited flag
+        u32 r = 0;
+        for (u32 j = 0; j < nc; ++j) r += ((mine[j] & ~1ull) < k) ? 1u : 0u;
+        sorted[r] = k;
+    }
+    __syncthreads();
+    if (nc > efC) nc = efC;
+    u32 nk = 0;
+    u32 my_id = PAG_EMPTY;       // lane s holds kept[s]
+    u32 my_key = 0;
+    for (u32 ci = 0; ci < nc && nk < L.deg; ++ci) {
+        const u64 k = sorted[ci];
+        const u32 c = (u32)(k & 0xFFFFFFFFull) >> 1;
+        const float dvc = __uint_as_float((u32)(k >> 32));
+        stage(vec, L.d, c, sv, lane);
+        __syncthreads();
+        bool occluded = false;
+        for (u32 s = 0; s < nk && !occluded; ++s) {
+            const float dsc = dist_lds(vec, L.d, sv, kept[s], lane);
+            occluded = dsc <= dvc;
+        }
+        if (!occluded) {
+            if ((u32)lane == nk) { my_id = c; my_key = (u32)(k >> 32); kept[nk] = c; }
+            nk++;
+        }
+        __syncthreads();
+    }
+    u32* ids = (u32*)(recs + (u64)v * L.rec_bytes);
+    if ((u32)lane < L.deg) {
+        ids[lane] = my_id;
+        const u64 o = (u64)vi * L.deg + lane;
+        rev_keys[o] = my_id == PAG_EMPTY ? PAG_KEY_INVALID : (((u64)my_id << 32) | my_key);
+        rev_vals[o] = v;
+    }
+}
+
+// ---- reverse edges, one wave per target (Sec. 2.1, N_in(v); Eq. 1) ----
+// Sorted pairs (target << 32 | dist bits, source).  The wave whose pair starts a target's segment
+// walks the segment.  For an incoming v at squared distance duv:
+//   refuse if some w in N_out(u) has ||w-u||^2 <= duv and ||w-v||^2 <= duv;
+//   else take a free slot; if the list is full, drop the neighbours farther than v that v now
+//   occludes (||v-f||^2 <= ||f-u||^2), or failing that the farthest of N_out(u) + {v}.
+// Every slot that received a new neighbour is appended to `edges` for the inference-information pass.
+__global__ void __launch_bounds__(64) k_reverse(const float* __restrict__ vec, uint8_t* __restrict__ recs,
+                                                float* __restrict__ e2, pag_layout L,
+                                                const u64* __restrict__ keys, const u32* __restrict__ vals,
+                                                u32 n_pairs, u32* __restrict__ edges, u32* __restrict__ n_edges) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sv = (float*)smem;
+    const u32 i0 = blockIdx.x;
+    if (i0 >= n_pairs) return;
+    const u64 k0 = keys[i0];
+    if (k0 == PAG_KEY_INVALID) return;
+    const u32 u = (u32)(k0 >> 32);
+    if (i0 > 0 && (u32)(keys[i0 - 1] >> 32) == u) return;       // not the head of its segment
+    const int lane = threadIdx.x;
+    uint8_t* rec = recs + (u64)u * L.rec_bytes;
+    u32 id = PAG_EMPTY;
+    float we2 = 0.f;
+    if ((u32)lane < L.deg) { id = ((const u32*)rec)[lane]; we2 = e2[(u64)u * L.deg + lane]; }
+    u64 changed = 0;
+    for (u32 i = i0; i < n_pairs; ++i) {
+        const u64 k = keys[i];
+        if (k == PAG_KEY_INVALID || (u32)(k >> 32) != u) break;
+        const u32 v = vals[i];
+        const float duv = __uint_as_float((u32)(k & 0xFFFFFFFFull));
+        const bool valid = (u32)lane < L.deg && id != PAG_EMPTY;
+        if (__ballot(valid && id == v)) continue;
+        stage(vec, L.d, v, sv, lane);
+        __syncthreads();
+        // lane s gets ||w_s - v||^2
+        float dwv = 0.f;
+        for (u64 mm = __ballot(valid); mm;) {
+            const int p = __ffsll((long long)mm) - 1;
+            mm &= mm - 1;
+            const u32 w = (u32)__builtin_amdgcn_readlane((int)id, p);
+            const float dd = dist_lds(vec, L.d, sv, w, lane);
+            if (lane == p) dwv = dd;
+        }
+        __syncthreads();
+        if (__ballot(valid && we2 <= duv && dwv <= duv)) continue;                 // Eq. 1: v is occluded
+        const u64 freem = __ballot((u32)lane < L.deg && id == PAG_EMPTY);
+        int slot = -1;
+        if (freem) {
+            slot = __ffsll((long long)freem) - 1;
+        } else {
+            const bool farther = we2 > duv || (we2 == duv && id > v);
+            const u64 dropm = __ballot(valid && farther && dwv <= we2);
+            if (dropm) {
+                slot = __ffsll((long long)dropm) - 1;
+                if ((dropm >> lane) & 1ull) { id = PAG_EMPTY; we2 = 0.f; }
+            } else {
+                // farthest neighbour by (e2, id)
+                u64 fk = valid ? (((u64)__float_as_uint(we2) << 32) | id) : 0ull;
+                u64 best = fk;
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) {
+                    const u64 other = __shfl_xor(best, o, 64);
+                    best = other > best ? other : best;
+                }
+                const u64 vk = ((u64)__float_as_uint(duv) << 32) | v;
+                if (vk < best) slot = __ffsll((long long)__ballot(valid && fk == best)) - 1;
+            }
+        }
+        if (slot >= 0) {
+            if (lane == slot) { id = v; we2 = duv; }
+            changed |= 1ull << slot;
+        }
+    }
+    if ((u32)lane < L.deg) {
+        ((u32*)rec)[lane] = id;
+        e2[(u64)u * L.deg + lane] = we2;
+        if (id == PAG_EMPTY) {                                // a dropped neighbour leaves a clean slot
+            ((float*)(rec + L.off_a))[lane] = 0.f;
+            ((float*)(rec + L.off_c))[lane] = 0.f;
+        }
+    }
+    const u32 nch = (u32)__popcll(changed);
+    if (nch) {
+        u32 base = 0;
+        if (lane == 0) base = atomicAdd(n_edges, nch);
+        base = (u32)__builtin_amdgcn_readfirstlane((int)base);
+        if ((changed >> lane) & 1ull) {
+            const u32 idx = base + (u32)__popcll(changed & ((1ull << lane) - 1));
+            edges[2 * (u64)idx] = u;
+            edges[2 * (u64)idx + 1] = (u32)lane;
+        }
+    }
+}
+
+struct BuildWs {
+    u64* cand = nullptr; u32* cand_cnt = nullptr;
+    u64 *rk_in = nullptr, *rk_out = nullptr; u32 *rv_in = nullptr, *rv_out = nullptr;
+    u32* edges = nullptr; u32* n_edges = nullptr;
+    void* sort_tmp = nullptr; size_t sort_bytes = 0;
+    ~BuildWs() {
+        void* p[] = { cand, cand_cnt, rk_in, rk_out, rv_in, rv_out, edges, n_edges, sort_tmp };
+        for (void* x : p) if (x) (void)hipFree(x);
+    }
+};
+
+#define PAG_ALLOC(ptr, bytes)                                                                   \
+    do {                                                                                        \
+        hipError_t e__ = hipMalloc((void**)&(ptr), (bytes) ? (bytes) : 16);                      \
+        if (e__ != hipSuccess) { pag_set_error(std::string("hipMalloc (build): ") + hipGetErrorString(e__)); return PAG_ENOMEM; } \
+    } while (0)
+
+}  // namespace
+
+int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
+    if (n_end <= n_begin) return PAG_OK;
+    const pag_layout& L = ix->L;
+    hipStream_t s = ix->stream;
+    const u32 b = std::min<u32>(ix->efC, 100);
+    const u32 Rmax = std::max<u32>(1, (ix->efC + b - 1) / b);
+    const u32 cand_cap = Rmax * b;
+    int rc;
+    u64 pos = n_begin;
+    if (n_begin == 0) {
+        const u32 n_init = (u32)std::min<u64>(n_end, b);
+        if (n_init > 1) {
+            const u32 lds = L.d * 4 + 2 * n_init * 8;
+            hipLaunchKernelGGL(k_init_clique, dim3(n_init), dim3(64), lds, s, ix->vec, ix->rec, L, n_init);
+            PAG_HIP(hipGetLastError());
+            if ((rc = pag_launch_edge_info_nodes(s, ix, 0, n_init))) return rc;
+        }
+        pos = n_init;
+        // the search kernel reads entry ids from device memory: ids 0 .. min(n, 1024) - 1
+        std::vector<u32> e(1024);
+        for (u32 i = 0; i < 1024; ++i) e[i] = i;
+        PAG_HIP(hipMemcpyAsync(ix->entry, e.data(), 1024 * 4, hipMemcpyHostToDevice, s));
+        PAG_HIP(hipStreamSynchronize(s));
+    }
+    if (pos >= n_end) { PAG_HIP(hipStreamSynchronize(s)); return PAG_OK; }
+
+    u64 max_batch = ix->subbatch ? ix->subbatch : std::min<u64>(16384, std::max<u64>(1024, n_end / 50));
+    BuildWs ws;
+    PAG_ALLOC(ws.cand, max_batch * cand_cap * 8);
+    PAG_ALLOC(ws.cand_cnt, max_batch * 4);
+    const u64 max_pairs = max_batch * L.deg;
+    PAG_ALLOC(ws.rk_in, max_pairs * 8);
+    PAG_ALLOC(ws.rk_out, max_pairs * 8);
+    PAG_ALLOC(ws.rv_in, max_pairs * 4);
+    PAG_ALLOC(ws.rv_out, max_pairs * 4);
+    PAG_ALLOC(ws.edges, max_pairs * 8);
+    PAG_ALLOC(ws.n_edges, 16);
+    PAG_HIP(hipcub::DeviceRadixSort::SortPairs(nullptr, ws.sort_bytes, ws.rk_in, ws.rk_out, ws.rv_in, ws.rv_out,
+                                               (int)max_pairs, 0, 64, s));
+    PAG_ALLOC(ws.sort_tmp, ws.sort_bytes);
+    {   // table workspace for the largest batch
+        const u64 need = max_batch * L.Ppad * PAG_NCODE;
+        if (ix->ws_tab_cap < need) {
+            if (ix->ws_tab) (void)hipFree(ix->ws_tab);
+            ix->ws_tab = nullptr; ix->ws_tab_cap = 0;
+            PAG_ALLOC(ix->ws_tab, need * 4);
+            ix->ws_tab_cap = need;
+        }
+    }
+    struct FlagGuard {   // indexing always runs with the projection test on
+        pag_index* ix; u32 saved;
+        explicit FlagGuard(pag_index* i) : ix(i), saved(i->flags) { i->flags &= ~PAG_FLAG_NO_PRT; }
+        ~FlagGuard() { ix->flags = saved; }
+    } flag_guard(ix);
+    while (pos < n_end) {
+        u64 m = std::min<u64>(n_end - pos, max_batch);
+        m = std::min<u64>(m, std::max<u64>(1, pos / 2));
+        // 1. projection tables of the new nodes (they are their own queries, already rotated)
+        const float* qrot = ix->vec + pos * L.d;
+        if ((rc = pag_launch_tables(s, qrot, m, L, ix->cb, ix->ws_tab))) return rc;
+        // 2. PRT-TFB search of the graph of nodes [0, pos)
+        SearchArgs a;
+        u32 lds = 0;
+        int grid = 0;
+        ix->n_entry = (u32)std::min<u64>(pos, 1024);
+        if ((rc = pag_search_common(ix, b, ix->efC, pos, &a, &lds, &grid))) return rc;
+        a.qrot = qrot; a.tables = ix->ws_tab; a.nq = (u32)m; a.K = b;
+        a.cand = ws.cand; a.cand_cnt = ws.cand_cnt; a.cand_cap = cand_cap;
+        if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
+        if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
+        // 3. RobustPrune -> N_out(v), reverse pairs
+        {
+            const u32 plds = L.d * 4 + cand_cap * 8 + L.deg * 4;
+            hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, ix->vec, ix->rec, L, (u32)pos, (u32)m,
+                               ws.cand, ws.cand_cnt, cand_cap, ix->efC, ws.rk_in, ws.rv_in);
+            PAG_HIP(hipGetLastError());
+        }
+        // 4. group reverse pairs by target
+        const u32 n_pairs = (u32)(m * L.deg);
+        PAG_HIP(hipcub::DeviceRadixSort::SortPairs(ws.sort_tmp, ws.sort_bytes, ws.rk_in, ws.rk_out, ws.rv_in, ws.rv_out,
+                                                   (int)n_pairs, 0, 64, s));
+        // 5. apply them
+        if ((rc = pag_launch_zero_u32(s, ws.n_edges, 1))) return rc;
+        hipLaunchKernelGGL(k_reverse, dim3(n_pairs), dim3(64), L.d * 4, s, ix->vec, ix->rec, ix->e2, L, ws.rk_out,
+                           ws.rv_out, n_pairs, ws.edges, ws.n_edges);
+        PAG_HIP(hipGetLastError());
+        // 6. inference information of the new forward edges and of every changed reverse slot
+        if ((rc = pag_launch_edge_info_nodes(s, ix, pos, pos + m))) return rc;
+        u32 n_edges = 0;
+        PAG_HIP(hipMemcpyAsync(&n_edges, ws.n_edges, 4, hipMemcpyDeviceToHost, s));
+        PAG_HIP(hipStreamSynchronize(s));
+        if ((rc = pag_launch_edge_info_list(s, ix, ws.edges, n_edges))) return rc;
+        pos += m;
+    }
+    PAG_HIP(hipStreamSynchronize(s));
+    return PAG_OK;
+}

@@ -1,0 +1,115 @@
+// Internal declarations shared by the translation units of the PAG library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "pag.h"
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+
+#define PAG_EMPTY 0xFFFFFFFFu
+#define PAG_NCODE 16        // projection vectors per subspace (Appendix D (1)): one code is 4 bits
+#define PAG_KEY_INVALID 0xFFFFFFFFFFFFFFFFull
+#define PAG_MAX_B 128       // working-set size limit: two entries per lane
+#define PAG_MAX_DEG 64      // one neighbour per lane
+#define PAG_MAX_CW 8        // code dwords per neighbour: up to 64 subspaces
+
+void pag_set_error(const std::string& msg);
+
+#define PAG_HIP(call)                                                                        \
+    do {                                                                                     \
+        hipError_t e__ = (call);                                                             \
+        if (e__ != hipSuccess) {                                                             \
+            pag_set_error(std::string(#call) + ": " + hipGetErrorString(e__));               \
+            return PAG_EHIP;                                                                 \
+        }                                                                                    \
+    } while (0)
+
+// Device-side statistics, summed with atomics by every wave when it retires.
+enum {
+    CTR_QUERIES = 0, CTR_HOPS, CTR_TESTS, CTR_PASSES, CTR_EXACT, CTR_ROUNDS, CTR_RF_OVER,
+    CTR_RT_OVER, CTR_SPILLS, CTR_COUNT
+};
+
+// Adjacency record of node u (one burst of whole 128-byte lines):
+//   [ids deg x u32][a deg x f32][c deg x f32][codes deg x (cw dwords)]   padded to 128 bytes
+// codes of neighbour slot s: dword l/8 of its chunk holds the code of subspace l in bits 4*(l%8).
+struct pag_layout {
+    u32 d, P, dsub, deg;
+    u32 Ppad;        // P rounded up to a multiple of 16 (table rows beyond P are zero)
+    u32 cw;          // code dwords per neighbour = Ppad / 8
+    u32 rec_bytes;   // record size
+    u32 off_a, off_c, off_codes;
+};
+
+struct pag_index {
+    int device;
+    hipStream_t stream;
+    pag_layout L;
+    int32_t metric;
+    u64 n, capacity;
+    u32 efC, search_b, subbatch, flags, seen_log2;
+    u64 seed;
+    // HBM-resident index
+    float* vec;      // [capacity * d]   rotated vectors
+    uint8_t* rec;    // [capacity * rec_bytes]
+    float* e2;       // [capacity * deg] ||w-u||^2 per edge (indexing only)
+    float* rot;      // [d * d]          Q (row-major)
+    float* cb;       // [P * 16 * dsub]
+    u32* entry;      // [n_entry]
+    u32 n_entry;
+    // workspaces (grown on demand, kept between calls)
+    float* ws_qrot;  u64 ws_qrot_cap;     // floats
+    float* ws_tab;   u64 ws_tab_cap;      // floats
+    float* ws_norm;  u64 ws_norm_cap;     // floats (normalised copies for COS)
+    u32* ws_bitmap;  u64 ws_bitmap_cap;   // u32 words: per-wave seen-set spill bitmaps
+    u32* d_qcounter;                      // persistent-wave work counter
+    u64* d_counters;                      // CTR_COUNT
+    hipEvent_t ev[4];
+    int num_cu;
+    double last_search_ms, last_prepare_ms, last_build_ms;
+};
+
+struct SearchArgs {
+    const float* vec;
+    const uint8_t* rec;
+    const float* qrot;       // [nq * d] rotated queries
+    const float* tables;     // [nq * Ppad * 16]
+    const u32* entry;
+    u32 n_entry;
+    u32 n_limit;             // only nodes < n_limit belong to the graph
+    u32 d, deg, Ppad, cw, rec_bytes, off_a, off_c, off_codes;
+    u32 nq, K, b, Rmax, hlog, flags;
+    u32 off_hash, off_sa, off_sb, off_rf, off_rt;   // LDS offsets (bytes)
+    long long* out_ids;      // [nq * K]       (search mode)
+    float* out_dists;        // [nq * K]
+    float out_scale;         // 1 for L2, 0.5 for IP / COS
+    u64* cand;               // [nq * cand_cap] keys of R_L (indexing mode), sorted per round
+    u32* cand_cnt;           // [nq]
+    u32 cand_cap;
+    u32* qcounter;
+    u64* counters;
+    u32* bitmap;             // [grid * bitmap_words]
+    u64 bitmap_words;
+};
+
+// kernels / launchers (defined in the .hip files)
+int pag_launch_search(const pag_index* ix, const SearchArgs& a, u32 lds_bytes, int* grid_out);
+int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, SearchArgs* a);
+int pag_search_max_grid(const pag_index* ix, u32 b, u32 lds_bytes, int* grid);
+
+int pag_launch_rotate(hipStream_t s, const float* X, u64 rows, u32 d, const float* rot, float* out);
+int pag_launch_tables(hipStream_t s, const float* qrot, u64 rows, const pag_layout& L, const float* cb, float* tables);
+int pag_launch_normalise(hipStream_t s, const float* X, u64 rows, u32 d, float* out);
+int pag_launch_zero_u32(hipStream_t s, u32* p, u64 count);
+int pag_launch_exact(hipStream_t s, const pag_index* ix, const float* qrot, u64 nq, const u32* ids, u32 m, float* keys);
+int pag_launch_screen(hipStream_t s, const pag_index* ix, const float* tables, u64 nq, const u32* u, const float* Du, float* est);
+int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begin, u64 node_end);
+int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edge_list, u64 n_edges);
+
+int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid);
+int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end);   // batch-synchronous insertion of nodes [n_begin, n_end)

@@ -1,0 +1,155 @@
+// Query / data preparation kernels: normalisation (cosine), rotation by the fixed orthogonal
+// transform Q (Alg. 1 "replace every x by Qx", Alg. 2 "q <- Qq") and the projection tables
+// (Alg. 2 "compute all <q_l, r_jl>").  All sums are fp64 sums of exact fp32 x fp32 products,
+// rounded once to fp32, so that they agree with a plain fp64 evaluation to the last bit in all
+// but a vanishing fraction of the outputs.
+#include "pag_internal.h"
+
+namespace {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------
+// Rotation: OUT[i][j] = fl32( sum_k X[i][k] * R[j][k] ),  X [rows x d], R [d x d] row-major.
+// The one dense contraction of the path: fp64 MFMA (v_mfma_f64_16x16x4), 64 x 64 output tile
+// per workgroup of 4 waves, each wave a 32 x 32 sub-tile (2 x 2 MFMA tiles), K staged through
+// LDS in steps of 32 as doubles.  Rows of the LDS tiles are padded to 36 doubles (72 dwords,
+// = 8 mod 64 banks) so that the 16 rows x 4 k-columns read by one MFMA operand fetch spread
+// over all banks.
+// ---------------------------------------------------------------------------------------
+constexpr int BM = 64, BN = 64, KT = 32, LDT = 36;
+
+__global__ void __launch_bounds__(256) k_rotate(const float* __restrict__ X, u64 rows, u32 d,
+                                                const float* __restrict__ R, float* __restrict__ OUT) {
+    __shared__ double As[BM][LDT];
+    __shared__ double Bs[BN][LDT];
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int wm = w >> 1, wn = w & 1;
+    const u64 m0 = (u64)blockIdx.y * BM;
+    const u32 n0 = blockIdx.x * BN;
+    double4_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = (double4_t){0.0, 0.0, 0.0, 0.0};
+
+    for (u32 k0 = 0; k0 < d; k0 += KT) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int idx = t + 256 * i, row = idx >> 3, k4 = (idx & 7) * 4;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), bb = a;
+            if (m0 + row < rows && k0 + k4 < d) a = *(const float4*)(X + (m0 + row) * d + k0 + k4);
+            if (n0 + row < d && k0 + k4 < d) bb = *(const float4*)(R + (u64)(n0 + row) * d + k0 + k4);
+            As[row][k4 + 0] = (double)a.x; As[row][k4 + 1] = (double)a.y;
+            As[row][k4 + 2] = (double)a.z; As[row][k4 + 3] = (double)a.w;
+            Bs[row][k4 + 0] = (double)bb.x; Bs[row][k4 + 1] = (double)bb.y;
+            Bs[row][k4 + 2] = (double)bb.z; Bs[row][k4 + 3] = (double)bb.w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < KT; kk += 4) {
+            const int r = lane & 15, kq = kk + (lane >> 4);
+            const double a0 = As[wm * 32 + r][kq], a1 = As[wm * 32 + 16 + r][kq];
+            const double b0 = Bs[wn * 32 + r][kq], b1 = Bs[wn * 32 + 16 + r][kq];
+            acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // accumulator layout of the 16x16 f64 tile: register r of lane l holds row l/16 + 4*r, column l%16
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const u64 row = m0 + wm * 32 + i * 16 + (lane >> 4) + 4 * r;
+                const u32 col = n0 + wn * 32 + j * 16 + (lane & 15);
+                if (row < rows && col < d) OUT[row * d + col] = (float)acc[i][j][r];
+            }
+}
+
+// tables[row][l][j] = fl32( sum_k r_jl[k] * q_l[k] ), k ascending; rows l >= P are zero padding.
+__global__ void __launch_bounds__(256) k_tables(const float* __restrict__ qrot, u64 rows, u32 d, u32 P,
+                                                u32 Ppad, u32 dsub, const float* __restrict__ cb,
+                                                float* __restrict__ tables) {
+    const u64 gid = (u64)blockIdx.x * 256 + threadIdx.x;
+    const u64 per_row = (u64)Ppad * PAG_NCODE;
+    if (gid >= rows * per_row) return;
+    const u64 row = gid / per_row;
+    const u32 lj = (u32)(gid % per_row), l = lj / PAG_NCODE;
+    float out = 0.f;
+    if (l < P) {
+        const float* r = cb + (u64)lj * dsub;
+        const float* q = qrot + row * d + (u64)l * dsub;
+        double acc = 0.0;
+        for (u32 k = 0; k < dsub; ++k) acc = __builtin_fma((double)r[k], (double)q[k], acc);
+        out = (float)acc;
+    }
+    tables[gid] = out;
+}
+
+// out = x / ||x||, one wave per row; norm from an fp64 sum of squares.
+__global__ void __launch_bounds__(64) k_normalise(const float* __restrict__ X, u64 rows, u32 d,
+                                                  float* __restrict__ out) {
+    const u64 row = blockIdx.x;
+    if (row >= rows) return;
+    const int lane = threadIdx.x;
+    const float* x = X + row * d;
+    double s = 0.0;
+    for (u32 k = lane; k < d; k += 64) s = __builtin_fma((double)x[k], (double)x[k], s);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    double nrm = sqrt(s);
+    if (nrm == 0.0) nrm = 1.0;
+    for (u32 k = lane; k < d; k += 64) out[row * d + k] = (float)((double)x[k] / nrm);
+}
+
+__global__ void __launch_bounds__(256) k_zero_u32(u32* p, u64 count) {
+    const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = 0u;
+}
+
+}  // namespace
+
+int pag_launch_rotate(hipStream_t s, const float* X, u64 rows, u32 d, const float* rot, float* out) {
+    if (rows == 0) return PAG_OK;
+    const u64 by = (rows + BM - 1) / BM;
+    // gridDim.y is limited to 65535: walk the rows in slabs
+    const u64 slab = 65535ull;
+    for (u64 y0 = 0; y0 < by; y0 += slab) {
+        const u64 ny = by - y0 < slab ? by - y0 : slab;
+        const u64 r0 = y0 * BM;
+        const u64 nrows = rows - r0 < ny * BM ? rows - r0 : ny * BM;
+        dim3 grid((d + BN - 1) / BN, (unsigned)ny);
+        hipLaunchKernelGGL(k_rotate, grid, dim3(256), 0, s, X + r0 * d, nrows, d, rot, out + r0 * d);
+    }
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
+}
+
+int pag_launch_tables(hipStream_t s, const float* qrot, u64 rows, const pag_layout& L, const float* cb,
+                      float* tables) {
+    if (rows == 0) return PAG_OK;
+    const u64 total = rows * L.Ppad * PAG_NCODE;
+    hipLaunchKernelGGL(k_tables, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, qrot, rows, L.d, L.P,
+                       L.Ppad, L.dsub, cb, tables);
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
+}
+
+int pag_launch_normalise(hipStream_t s, const float* X, u64 rows, u32 d, float* out) {
+    if (rows == 0) return PAG_OK;
+    hipLaunchKernelGGL(k_normalise, dim3((unsigned)rows), dim3(64), 0, s, X, rows, d, out);
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
+}
+
+int pag_launch_zero_u32(hipStream_t s, u32* p, u64 count) {
+    if (count == 0) return PAG_OK;
+    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, p, count);
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
+}

@@ -1,0 +1,61 @@
+// Launch logic of the search kernel: picks the instantiation for (d, b), sizes the per-wave LDS
+// carve-up and the persistent grid.
+#include "pag_internal.h"
+
+typedef void (*pag_search_fn)(const SearchArgs);
+pag_search_fn pag_search_fn_nq1(int);
+pag_search_fn pag_search_fn_nq2(int);
+pag_search_fn pag_search_fn_nq3(int);
+pag_search_fn pag_search_fn_nq4(int);
+pag_search_fn pag_search_fn_nq6(int);
+pag_search_fn pag_search_fn_nq8(int);
+pag_search_fn pag_search_fn_nq12(int);
+
+static pag_search_fn pick(u32 d, u32 b) {
+    const int nw = b <= 64 ? 1 : 2;
+    const u32 chunks = (d + 255) / 256;
+    if (chunks <= 1) return pag_search_fn_nq1(nw);
+    if (chunks <= 2) return pag_search_fn_nq2(nw);
+    if (chunks <= 3) return pag_search_fn_nq3(nw);
+    if (chunks <= 4) return pag_search_fn_nq4(nw);
+    if (chunks <= 6) return pag_search_fn_nq6(nw);
+    if (chunks <= 8) return pag_search_fn_nq8(nw);
+    if (chunks <= 12) return pag_search_fn_nq12(nw);
+    return nullptr;
+}
+
+static u32 align_up(u32 x, u32 a) { return (x + a - 1) / a * a; }
+
+// LDS carve-up of one wave; fills the offsets in `a` and returns the total.
+int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, SearchArgs* a) {
+    u32 off = align_up(L.Ppad * PAG_NCODE * 4, 16);
+    a->off_hash = off; off += (4u << hlog);
+    a->off_sa = off;   off += align_up(2 * b * 8, 16);
+    a->off_sb = off;   off += align_up(2 * b * 8, 16);
+    a->off_rf = off;   off += align_up(b * 8, 16);
+    a->off_rt = off;   off += align_up(b * 8, 16);
+    return (int)off;
+}
+
+int pag_search_max_grid(const pag_index* ix, u32 b, u32 lds_bytes, int* grid) {
+    pag_search_fn fn = pick(ix->L.d, b);
+    if (!fn) { pag_set_error("search: dimension above 3072 is not built"); return PAG_EUNSUPPORTED; }
+    int per_cu = 0;
+    PAG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)fn, 64, lds_bytes));
+    if (per_cu < 1) per_cu = 1;
+    *grid = per_cu * ix->num_cu;
+    return PAG_OK;
+}
+
+int pag_launch_search(const pag_index* ix, const SearchArgs& a, u32 lds_bytes, int* grid_io) {
+    pag_search_fn fn = pick(a.d, a.b);
+    if (!fn) { pag_set_error("search: dimension above 3072 is not built"); return PAG_EUNSUPPORTED; }
+    int grid = *grid_io;
+    if ((u64)grid > a.nq) grid = (int)a.nq;
+    if (grid < 1) return PAG_OK;
+    SearchArgs args = a;
+    void* kargs[] = { (void*)&args };
+    PAG_HIP(hipLaunchKernel((const void*)fn, dim3(grid), dim3(64), kargs, lds_bytes, ix->stream));
+    *grid_io = grid;
+    return PAG_OK;
+}

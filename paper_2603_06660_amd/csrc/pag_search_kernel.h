@@ -1,0 +1,465 @@
+// PRT-TFB best-first search (Alg. 2, Sec. 3.3): one wavefront owns one query from the
+// entry nodes to the final top-K.  Included by the per-NQ instantiation units.
+//
+// Wave-level data placement (64 lanes):
+//   query        registers, NQ float4 per lane (element chunk c*64+lane)
+//   W            registers, sorted ascending by key; rank r lives in slot r/64 of lane r%64
+//   R_L          registers, same placement (capacity K <= b)
+//   table T      LDS, float [Ppad][16]
+//   seen set     LDS open-addressing hash of node ids (exact); overflows into a per-wave HBM bitmap
+//   R_F, R_T     LDS rings of b keys each
+//   SA, SB       LDS scratch for scatters and rank sorts
+// A key packs (dist bits << 32) | (id << 1) | visited, so that unsigned comparison orders by
+// (dist, id); distances are sums of squares, hence non-negative and monotone as bit patterns.
+//
+// One hop evaluates the projection test for all neighbours of u at once, lane s <-> neighbour
+// slot s, against the threshold read when u is popped; the hop's passers enter W as if they
+// were admitted one after another in ascending (dist, id) order, which a merge by ranks
+// reproduces exactly: the b smallest of W + passers stay, displaced W members go to R_T
+// (largest first), passers that do not fit go to R_F (smallest first).
+#pragma once
+
+#include "pag_internal.h"
+
+namespace pagk {
+
+__device__ __forceinline__ u32 rdlane(u32 v, int l) { return (u32)__builtin_amdgcn_readlane((int)v, l); }
+__device__ __forceinline__ u64 rdlane64(u64 v, int l) {
+    u32 lo = rdlane((u32)v, l), hi = rdlane((u32)(v >> 32), l);
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ u32 uniform(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+__device__ __forceinline__ u32 hash_slot(u32 id, u32 hlog) { return (id * 2654435761u) >> (32 - hlog); }
+
+__device__ __forceinline__ bool hash_contains(const u32* H, u32 hlog, u32 id) {
+    const u32 mask = (1u << hlog) - 1;
+    u32 p = hash_slot(id, hlog);
+    for (;;) {
+        u32 v = H[p];
+        if (v == id) return true;
+        if (v == PAG_EMPTY) return false;
+        p = (p + 1) & mask;
+    }
+}
+
+__device__ __forceinline__ void hash_insert(u32* H, u32 hlog, u32 id) {
+    const u32 mask = (1u << hlog) - 1;
+    u32 p = hash_slot(id, hlog);
+    for (;;) {
+        u32 old = atomicCAS(&H[p], PAG_EMPTY, id);
+        if (old == PAG_EMPTY || old == id) return;
+        p = (p + 1) & mask;
+    }
+}
+
+// dst[rank] = src[i], rank = number of smaller keys; keys are distinct.  n <= 4 * 64.
+__device__ __forceinline__ void rank_sort(const u64* src, u64* dst, u32 n, int lane) {
+    for (u32 i = lane; i < n; i += 64) {
+        const u64 k = src[i];
+        u32 r = 0;
+        for (u32 j = 0; j < n; ++j) r += (src[j] < k) ? 1u : 0u;
+        dst[r] = k;
+    }
+}
+
+template <int NQ, int NW>
+struct Wave {
+    // constant for the kernel
+    const SearchArgs A;
+    const int lane;
+    float* T;
+    u32* H;
+    u64 *SA, *SB, *RF, *RT;
+    u32* bitmap;
+    // per query
+    float4 q[NQ];
+    u64 W[NW];
+    u64 RL[NW];
+    u32 nW, nRL;
+    u32 cntF, posF, cntT, posT;     // ring fill / next write position
+    u32 n_hash, n_spill;
+    // statistics (wave-uniform)
+    u32 s_hops, s_tests, s_passes, s_exact, s_rounds, s_rf, s_rt, s_spill, s_queries;
+
+    __device__ Wave(const SearchArgs& a, unsigned char* smem, int ln) : A(a), lane(ln) {
+        T = (float*)smem;
+        H = (u32*)(smem + a.off_hash);
+        SA = (u64*)(smem + a.off_sa);
+        SB = (u64*)(smem + a.off_sb);
+        RF = (u64*)(smem + a.off_rf);
+        RT = (u64*)(smem + a.off_rt);
+        bitmap = a.bitmap + (u64)blockIdx.x * a.bitmap_words;
+        s_hops = s_tests = s_passes = s_exact = s_rounds = s_rf = s_rt = s_spill = s_queries = 0;
+    }
+
+    __device__ __forceinline__ bool seen(u32 id) const {
+        if (hash_contains(H, A.hlog, id)) return true;
+        if (n_spill) {
+            u32 w = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return (w >> (id & 31)) & 1u;
+        }
+        return false;
+    }
+
+    // exact keys ||q - x_id||^2 (Alg. 2, "compute the distance") for the lanes in `mask`;
+    // lane p receives the key of its own id.  Differences in fp32, squares summed in fp64,
+    // one rounding to fp32 at the end.
+    __device__ __forceinline__ float exact_keys(u32 id_lane, u64 mask) {
+        constexpr int G = NQ <= 1 ? 8 : (NQ <= 4 ? 4 : (NQ <= 6 ? 2 : 1));
+        float mine = 0.f;
+        const u32 d = A.d;
+        while (mask) {
+            int pl[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (mask) { pl[g] = __ffsll((long long)mask) - 1; mask &= mask - 1; }
+                else pl[g] = -1;
+            }
+            float4 v[G][NQ];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (pl[g] >= 0) {
+                    const u32 id = rdlane(id_lane, pl[g]);
+                    const float4* p = (const float4*)(A.vec + (u64)id * d);
+#pragma unroll
+                    for (int c = 0; c < NQ; ++c) {
+                        const u32 idx = c * 64 + lane;
+                        if (c < NQ - 1 || idx * 4 < d) v[g][c] = p[idx];
+                        else v[g][c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (pl[g] >= 0) {
+                    double acc = 0.0;
+#pragma unroll
+                    for (int c = 0; c < NQ; ++c) {
+                        float dx = q[c].x - v[g][c].x, dy = q[c].y - v[g][c].y;
+                        float dz = q[c].z - v[g][c].z, dw = q[c].w - v[g][c].w;
+                        acc = __builtin_fma((double)dx, (double)dx, acc);
+                        acc = __builtin_fma((double)dy, (double)dy, acc);
+                        acc = __builtin_fma((double)dz, (double)dz, acc);
+                        acc = __builtin_fma((double)dw, (double)dw, acc);
+                    }
+                    acc = wave_sum(acc);
+                    if (lane == pl[g]) mine = (float)acc;
+                }
+            }
+        }
+        return mine;
+    }
+
+    // Admission of the lanes in `mask` (ids in id_lane): exact keys, seen-set insertion, merge into W.
+    __device__ __forceinline__ void admit(u32 id_lane, u64 mask) {
+        const u32 np = (u32)__popcll(mask);
+        if (np == 0) return;
+        const u32 b = A.b;
+        const bool pass = (mask >> lane) & 1ull;
+        const float dist = exact_keys(id_lane, mask);
+        s_exact += np;
+        // seen set
+        const bool spill = (n_hash + np) > (1u << (A.hlog - 1));
+        if (pass) {
+            if (!spill) hash_insert(H, A.hlog, id_lane);
+            else atomicOr(&bitmap[id_lane >> 5], 1u << (id_lane & 31));
+        }
+        if (spill) { n_spill += np; s_spill += np; } else n_hash += np;
+
+        const u64 pk = pass ? (((u64)__float_as_uint(dist) << 32) | ((u64)id_lane << 1)) : PAG_KEY_INVALID;
+        u32 cntW[NW];
+#pragma unroll
+        for (int s = 0; s < NW; ++s) cntW[s] = 0;
+        u32 cP = 0, cPW = 0;
+        for (u64 m = mask; m;) {
+            const int p = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const u64 k = rdlane64(pk, p);
+            u32 c = 0;
+#pragma unroll
+            for (int s = 0; s < NW; ++s) {
+                c += (u32)__popcll(__ballot(W[s] < k));
+                cntW[s] += (k < W[s]) ? 1u : 0u;
+            }
+            cP += (k < pk) ? 1u : 0u;
+            if (lane == p) cPW = c;
+        }
+        const u32 total = nW + np;
+        const u32 nW2 = total < b ? total : b;
+        const u32 rP = cP + cPW;                                   // merged rank of my passer
+        const u32 n_ins = (u32)__popcll(__ballot(pass && rP < b)); // passers that enter W
+        const u32 n_f = np - n_ins;                                // false positives -> R_F
+        const u32 n_ej = nW + n_ins - nW2;                         // displaced members -> R_T
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
+            const u32 idx = s * 64 + lane;
+            if (idx < nW) {
+                const u32 r = idx + cntW[s];
+                if (r < b) SA[r] = W[s];
+                else RT[(posT + (nW - 1 - idx)) % b] = W[s];       // largest first
+            }
+        }
+        if (pass) {
+            if (rP < b) SA[rP] = pk;
+            else {
+                const u32 oi = cP - n_ins;                          // smallest first
+                if (oi + b >= n_f) RF[(posF + oi) % b] = pk;        // older ones would be overwritten anyway
+            }
+        }
+        if (n_ej) {
+            if (cntT + n_ej > b) s_rt += cntT + n_ej - b;
+            cntT = cntT + n_ej < b ? cntT + n_ej : b;
+            posT = (posT + n_ej) % b;
+        }
+        if (n_f) {
+            if (cntF + n_f > b) s_rf += cntF + n_f - b;
+            cntF = cntF + n_f < b ? cntF + n_f : b;
+            posF = (posF + n_f) % b;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
+            const u32 idx = s * 64 + lane;
+            W[s] = idx < nW2 ? SA[idx] : PAG_KEY_INVALID;
+        }
+        nW = nW2;
+        __syncthreads();
+    }
+
+    __device__ __forceinline__ void run_query(u32 qi) {
+        const u32 d = A.d, b = A.b, deg = A.deg;
+        // ---- load query, table, reset state ----
+        {
+            const float4* qp = (const float4*)(A.qrot + (u64)qi * d);
+#pragma unroll
+            for (int c = 0; c < NQ; ++c) {
+                const u32 idx = c * 64 + lane;
+                q[c] = (c < NQ - 1 || idx * 4 < d) ? qp[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            const float4* tp = (const float4*)(A.tables + (u64)qi * A.Ppad * PAG_NCODE);
+            for (u32 i = lane; i < A.Ppad * PAG_NCODE / 4; i += 64) ((float4*)T)[i] = tp[i];
+            const uint4 e4 = make_uint4(PAG_EMPTY, PAG_EMPTY, PAG_EMPTY, PAG_EMPTY);
+            for (u32 i = lane; i < (1u << A.hlog) / 4; i += 64) ((uint4*)H)[i] = e4;
+#pragma unroll
+            for (int s = 0; s < NW; ++s) { W[s] = PAG_KEY_INVALID; RL[s] = PAG_KEY_INVALID; }
+            nW = nRL = 0;
+            cntF = posF = cntT = posT = 0;
+            n_hash = n_spill = 0;
+            __syncthreads();
+        }
+        s_queries++;
+        u32 n_cand = 0;   // indexing mode: entries of R_L written so far
+
+        // ---- b entry nodes (Alg. 2, "insert b entry nodes into W") ----
+        {
+            u32 ne = A.n_entry < b ? A.n_entry : b;
+            for (u32 base = 0; base < ne; base += 64) {
+                const u32 i = base + lane;
+                u32 id = PAG_EMPTY;
+                if (i < ne) id = A.entry[i];
+                const bool ok = id != PAG_EMPTY && id < A.n_limit;
+                admit(id, __ballot(ok));
+            }
+        }
+
+        // ---- rounds ----
+        for (u32 r = 0; r < A.Rmax; ++r) {
+            if (nW == 0) break;
+            s_rounds++;
+            for (;;) {
+                // closest unvisited member of W
+                int us = -1, ul = 0;
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    const u32 idx = s * 64 + lane;
+                    const u64 m = __ballot(idx < nW && !(W[s] & 1ull));
+                    if (us < 0 && m) { us = s; ul = __ffsll((long long)m) - 1; }
+                }
+                if (us < 0) break;
+                u64 ukey = 0;
+#pragma unroll
+                for (int s = 0; s < NW; ++s)
+                    if (s == us) {
+                        ukey = rdlane64(W[s], ul);
+                        if (lane == ul) W[s] |= 1ull;
+                    }
+                s_hops++;
+                const u32 u = (u32)(ukey & 0xFFFFFFFFull) >> 1;
+                const float Du = __uint_as_float((u32)(ukey >> 32));
+                // threshold ||z_max - q||^2, read once per hop (Eq. 4); +inf while W is not full
+                float Dmax = __builtin_inff();
+                if (nW == b) {
+                    const u32 wr = b - 1;
+#pragma unroll
+                    for (int s = 0; s < NW; ++s)
+                        if ((int)(wr >> 6) == s) Dmax = __uint_as_float(rdlane((u32)(W[s] >> 32), wr & 63));
+                }
+                // adjacency record of u
+                const uint8_t* rec = A.rec + (u64)u * A.rec_bytes;
+                u32 id = PAG_EMPTY;
+                float ea = 0.f, ec = 0.f;
+                u32 cwv[PAG_MAX_CW];
+#pragma unroll
+                for (int k = 0; k < PAG_MAX_CW; ++k) cwv[k] = 0;
+                if ((u32)lane < deg) {
+                    id = ((const u32*)rec)[lane];
+                    ea = ((const float*)(rec + A.off_a))[lane];
+                    ec = ((const float*)(rec + A.off_c))[lane];
+                    const u32* cp = (const u32*)(rec + A.off_codes) + (u32)lane * A.cw;
+#pragma unroll
+                    for (int k = 0; k < PAG_MAX_CW; k += 2) {
+                        if ((u32)k < A.cw) {
+                            const uint2 t = *(const uint2*)(cp + k);
+                            cwv[k] = t.x; cwv[k + 1] = t.y;
+                        }
+                    }
+                }
+                bool cand = id != PAG_EMPTY && id < A.n_limit;
+                if (cand) cand = !seen(id);
+                // projection test: S = sum_l T[l][code_l] (increasing l), est = D_u + c - 2 a S
+                bool pass = cand;
+                if (!(A.flags & PAG_FLAG_NO_PRT)) {
+                    float S = 0.f;
+                    if (cand) {
+#pragma unroll
+                        for (int k = 0; k < PAG_MAX_CW; ++k) {
+                            if ((u32)k < A.cw) {
+                                const u32 wd = cwv[k];
+#pragma unroll
+                                for (int t = 0; t < 8; ++t)
+                                    S = S + T[(k * 8 + t) * PAG_NCODE + ((wd >> (4 * t)) & 15u)];
+                            }
+                        }
+                    }
+                    const float est = __builtin_fmaf(-2.0f * ea, S, Du + ec);
+                    pass = cand && (est < Dmax);
+                }
+                const u64 cmask = __ballot(cand);
+                const u64 pmask = __ballot(pass);
+                s_tests += (u32)__popcll(cmask);
+                s_passes += (u32)__popcll(pmask);
+                admit(id, pmask);
+            }
+
+            // ---- round end (Alg. 2): W -> R_L, clear W; merge + sort rings; refill W; rest -> R_T ----
+            if (A.cand) {
+                // indexing: R_L has room for every round's W (capacity efC >= Rmax * b is enforced by the host)
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    const u32 idx = s * 64 + lane;
+                    if (idx < nW && n_cand + idx < A.cand_cap) A.cand[(u64)qi * A.cand_cap + n_cand + idx] = W[s];
+                }
+                n_cand = n_cand + nW < A.cand_cap ? n_cand + nW : A.cand_cap;
+            } else {
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    const u32 idx = s * 64 + lane;
+                    if (idx < nRL) SA[idx] = RL[s];
+                    if (idx < nW) SA[nRL + idx] = W[s];
+                }
+                __syncthreads();
+                const u32 n = nRL + nW;
+                rank_sort(SA, SB, n, lane);
+                __syncthreads();
+                nRL = n < A.K ? n : A.K;
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    const u32 idx = s * 64 + lane;
+                    RL[s] = idx < nRL ? SB[idx] : PAG_KEY_INVALID;
+                }
+                __syncthreads();
+            }
+            {
+                for (u32 i = lane; i < cntF; i += 64) SA[i] = RF[i];
+                for (u32 i = lane; i < cntT; i += 64) SA[cntF + i] = RT[i];
+                __syncthreads();
+                const u32 n = cntF + cntT;
+                rank_sort(SA, SB, n, lane);
+                __syncthreads();
+                nW = n < b ? n : b;
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    const u32 idx = s * 64 + lane;
+                    W[s] = idx < nW ? SB[idx] : PAG_KEY_INVALID;
+                }
+                const u32 rest = n - nW;                         // <= b; written worst first
+                for (u32 j = lane; j < rest; j += 64) RT[j] = SB[n - 1 - j];
+                cntT = rest; posT = rest % b;
+                cntF = 0; posF = 0;
+                __syncthreads();
+            }
+        }
+
+        // ---- output ----
+        if (A.cand) {
+            if (lane == 0) A.cand_cnt[qi] = n_cand;
+        } else {
+#pragma unroll
+            for (int s = 0; s < NW; ++s) {
+                const u32 idx = s * 64 + lane;
+                if (idx < A.K) {
+                    long long oid = -1;
+                    float od = __builtin_inff();
+                    if (idx < nRL) {
+                        oid = (long long)((u32)(RL[s] & 0xFFFFFFFFull) >> 1);
+                        od = A.out_scale * __uint_as_float((u32)(RL[s] >> 32));
+                    }
+                    A.out_ids[(u64)qi * A.K + idx] = oid;
+                    A.out_dists[(u64)qi * A.K + idx] = od;
+                }
+            }
+        }
+        // a spilled query leaves its bitmap clean for the next one
+        if (n_spill) {
+            uint4* bm = (uint4*)bitmap;
+            const uint4 z = make_uint4(0, 0, 0, 0);
+            for (u64 i = lane; i < A.bitmap_words / 4; i += 64) bm[i] = z;
+            __threadfence();
+        }
+    }
+
+    __device__ __forceinline__ void flush_stats() {
+        if (lane == 0) {
+            atomicAdd(&A.counters[CTR_QUERIES], (u64)s_queries);
+            atomicAdd(&A.counters[CTR_HOPS], (u64)s_hops);
+            atomicAdd(&A.counters[CTR_TESTS], (u64)s_tests);
+            atomicAdd(&A.counters[CTR_PASSES], (u64)s_passes);
+            atomicAdd(&A.counters[CTR_EXACT], (u64)s_exact);
+            atomicAdd(&A.counters[CTR_ROUNDS], (u64)s_rounds);
+            atomicAdd(&A.counters[CTR_RF_OVER], (u64)s_rf);
+            atomicAdd(&A.counters[CTR_RT_OVER], (u64)s_rt);
+            atomicAdd(&A.counters[CTR_SPILLS], (u64)s_spill);
+        }
+    }
+};
+
+// Persistent waves: every wave pulls query numbers from one counter until the batch is drained,
+// so long and short searches balance themselves; the loop ends for every wave once the counter
+// passes nq.
+template <int NQ, int NW>
+__global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x;
+    Wave<NQ, NW> w(A, smem, lane);
+    for (;;) {
+        u32 qi = 0;
+        if (lane == 0) qi = atomicAdd(A.qcounter, 1u);
+        qi = uniform(qi);
+        if (qi >= A.nq) break;
+        w.run_query(qi);
+    }
+    w.flush_stats();
+}
+
+}  // namespace pagk
+
+#define PAG_INSTANTIATE_SEARCH(NQ)                                                          \
+    template __global__ void pagk::k_search<NQ, 1>(const SearchArgs);                      \
+    template __global__ void pagk::k_search<NQ, 2>(const SearchArgs);

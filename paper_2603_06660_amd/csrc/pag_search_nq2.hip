@@ -1,0 +1,7 @@
+// Instantiation of the search kernel for vectors of up to 512 floats (2 float4 per lane).
+#include "pag_search_kernel.h"
+
+typedef void (*pag_search_fn)(const SearchArgs);
+pag_search_fn pag_search_fn_nq2(int nw) {
+    return nw == 1 ? (pag_search_fn)pagk::k_search<2, 1> : (pag_search_fn)pagk::k_search<2, 2>;
+}

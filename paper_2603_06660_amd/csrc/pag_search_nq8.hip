@@ -1,0 +1,7 @@
+// Instantiation of the search kernel for vectors of up to 2048 floats (8 float4 per lane).
+#include "pag_search_kernel.h"
+
+typedef void (*pag_search_fn)(const SearchArgs);
+pag_search_fn pag_search_fn_nq8(int nw) {
+    return nw == 1 ? (pag_search_fn)pagk::k_search<8, 1> : (pag_search_fn)pagk::k_search<8, 2>;
+}
