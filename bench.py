@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the PAG search hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 2] [--n N] [--nq NQ] [--efc EFC]
+
+A "step" is one pag_search call over the whole query batch of the workload (query rotation,
+projection tables and the fused best-first search), queries and results resident in HBM.
+The workload is configuration 2 of the synthetic set (n = 1,000,000, d = 768, inner product on
+unit vectors, degree 32, 32 subspaces, K = 10): the index is built on the GPU by pag_build, the
+efS grid is swept against brute-force ground truth, and the timed steps run at the smallest efS
+whose recall@10 reaches 0.95.  One JSON line is printed:
+  value        whole-batch queries per second over the timed steps
+  roofline     algorithmic HBM bytes of the search kernel / its HIP-event duration, against 8 TB/s
+  cpu_baseline the CPU oracle searching the same exported index with the same efS on a bounded
+               sample of the queries, on the host cores of this machine
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+TARGET_RECALL = 0.95
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(c, d, K):
+    """Bytes the method itself must move (Sec. 4.2's terms): per query the query vector and the
+    results, per expanded node its adjacency record, per exact distance one base vector."""
+    return (c["queries"] * (4 * d + 8 * K) + c["hops"] * c["adj_record_bytes"] + c["exact"] * 4 * d)
+
+
+def read_traffic(tag):
+    """HBM bytes per search-kernel launch from the committed rocprofv3 counter summary, if it covers this run."""
+    path = os.path.join(ROOT, "profiles", "search_kernel_%s_hbm_traffic.txt" % tag)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--cfg", type=int, default=2)
+    ap.add_argument("--n", type=int, default=None)
+    ap.add_argument("--nq", type=int, default=None)
+    ap.add_argument("--efc", type=int, default=1000)
+    ap.add_argument("--efs", type=int, default=0, help="skip the sweep and time this efS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="also launch one elementwise kernel of known size (1 GiB read, 1 GiB written) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import pag_workloads as wl
+    from paper_2603_06660_amd import PagIndex, load_library
+
+    load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.workload(args.cfg, n=args.n, nq=args.nq)
+    metric = {0: "l2", 1: "ip", 2: "cos"}[w.metric]
+
+    t0 = time.time()
+    base = wl.make(w, "base")
+    q = wl.make(w, "query")
+    log("generated %s: base %s, queries %s in %.1f s" % (w.name, base.shape, q.shape, time.time() - t0))
+    base_d = torch.from_numpy(base).cuda()
+    q_d = torch.from_numpy(q).cuda()
+    del base
+
+    t0 = time.time()
+    ix = PagIndex.build(base_d, metric=metric, max_degree=w.deg, num_subspaces=w.P, ef_construction=args.efc,
+                        seed=2603)
+    build_s = time.time() - t0
+    log("pag_build: %.2f s (%.0f vectors/s)" % (build_s, w.n / build_s))
+
+    t0 = time.time()
+    gt, _ = wl.brute_force_torch(base_d, q_d, w.K, w.metric)
+    log("ground truth: %.1f s" % (time.time() - t0))
+    del base_d
+    torch.cuda.empty_cache()
+
+    # ---- efS sweep: smallest efS of the grid with recall@K >= 0.95 ----
+    curve = []
+    chosen = None
+    # the configuration's grid, continued upwards: this synthetic set needs more than efS = 512
+    grid = (args.efs,) if args.efs else tuple(w.efs_grid) + tuple(
+        e for e in (640, 768, 896, 1024, 1280, 1536, 1792, 2048, 2560, 3072, 4096) if e > max(w.efs_grid))
+    for efS in grid:
+        ix.reset_counters()
+        t1 = time.time()
+        ids, dists = ix.search(q_d, w.K, efS)
+        dt = time.time() - t1
+        rec = wl.recall_at_k(ids.cpu().numpy(), gt)
+        c = ix.counters()
+        curve.append({"efS": efS, "recall": round(rec, 4), "qps_single_call": round(w.nq / dt, 1),
+                      "hops_per_query": round(c["hops"] / w.nq, 1), "exact_per_query": round(c["exact"] / w.nq, 1),
+                      "gamma": round(c["passes"] / max(1, c["tests"]), 4)})
+        log("efS %4d: recall@%d %.4f, %.0f QPS (one call), hops/q %.1f, exact/q %.1f, pass ratio %.3f" %
+            (efS, w.K, rec, w.nq / dt, c["hops"] / w.nq, c["exact"] / w.nq, c["passes"] / max(1, c["tests"])))
+        if chosen is None and rec >= TARGET_RECALL:
+            chosen = (efS, rec)
+            if not args.efs:
+                break
+    reached = chosen is not None
+    if chosen is None:
+        chosen = (curve[-1]["efS"], curve[-1]["recall"])
+        log("recall %.2f not reached on the grid; timing the largest efS" % TARGET_RECALL)
+    efS, recall = chosen
+
+    if args.pmc_probe:
+        x = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        y = torch.empty_like(x)
+        torch.add(x, 1.0, out=y)
+        torch.cuda.synchronize()
+        del x, y
+
+    # ---- timed region ----
+    ids = torch.empty((w.nq, w.K), dtype=torch.int64, device="cuda")
+    dists = torch.empty((w.nq, w.K), dtype=torch.float32, device="cuda")
+    for _ in range(args.warmup):
+        ix.search(q_d, w.K, efS, out=(ids, dists))
+    ix.reset_counters()
+    kernel_ms = []
+    prep_ms = []
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        ix.search(q_d, w.K, efS, out=(ids, dists))
+        # HIP-event durations recorded by the library on its own stream around the kernels of this call
+        c = ix.counters()
+        kernel_ms.append(c["last_search_kernel_ms"])
+        prep_ms.append(c["last_prepare_ms"])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    c = ix.counters()
+    ms_per_step = 1e3 * elapsed / args.steps
+    qps = w.nq * args.steps / elapsed
+    bytes_per_launch = algorithmic_bytes(c, w.d, w.K) / args.steps
+    k_ms = float(np.mean(kernel_ms))
+    achieved = bytes_per_launch / (k_ms * 1e-3) / 1e9
+    tag = "cfg%d" % w.cfg if (args.n is None and args.nq is None) else "custom"
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(tag),
+                "kernel": "pagk::k_search", "kernel_ms": round(k_ms, 4), "prepare_ms": round(float(np.mean(prep_ms)), 4),
+                "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+
+    # ---- CPU oracle on the same index, same efS, bounded sample ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import pag_oracle as orc
+        ex = ix.export()
+        oix = orc.OracleIndex(ex["vectors"], ex["adj"], ex["a"], ex["c"], ex["e2"], ex["codes"], ex["rotation"],
+                              ex["codebooks"], ex["entry"], metric=ex["metric"])
+        cores = min(16, os.cpu_count() or 1)
+        probe = min(w.nq, 2 * cores)
+        t2 = time.perf_counter()
+        oix.search(q[:probe], w.K, efS, threads=cores)
+        per_q = (time.perf_counter() - t2) / probe
+        sample = int(max(probe, min(w.nq, args.cpu_seconds / max(per_q, 1e-9))))
+        t2 = time.perf_counter()
+        oi, od, oc = oix.search(q[:sample], w.K, efS, threads=cores)
+        dt = time.perf_counter() - t2
+        agree = float((oi == ids[:sample].cpu().numpy()).mean())
+        cpu = {"value": round(sample / dt, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
+               "sample": "first %d of %d queries, same exported index, efS=%d; id-slot agreement with the GPU %.5f"
+                         % (sample, w.nq, efS, agree)}
+        log("cpu oracle: %.1f QPS on %d threads over %d queries; GPU/oracle id agreement %.5f" %
+            (sample / dt, cores, sample, agree))
+
+    out = {
+        "metric": "batched QPS at recall@10>=0.95 (1 GPU)", "value": round(qps, 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "cfg%d %s: n=%d d=%d nq=%d K=%d deg=%d P=%d efC=%d" %
+                               (w.cfg, w.name, w.n, w.d, w.nq, w.K, w.deg, w.P, args.efc),
+                   "efS": efS, "efS_within_configured_grid": bool(efS <= max(w.efs_grid)),
+                   "recall_at_10": round(recall, 4), "recall_target_reached": reached,
+                   "skipped_fraction": round(1.0 - c["passes"] / max(1, c["tests"]), 4),
+                   "hops_per_query": round(c["hops"] / max(1, c["queries"]), 1),
+                   "exact_per_query": round(c["exact"] / max(1, c["queries"]), 1),
+                   "build_seconds": round(build_s, 2), "sweep": curve},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -203,3 +203,38 @@ def recall_at_k(found_ids: np.ndarray, true_ids: np.ndarray) -> float:
     for r in range(nq):
         hit += len(set(found_ids[r, :K].tolist()) & set(true_ids[r].tolist()))
     return hit / float(nq * K)
+
+
+def brute_force_torch(base_t, queries_t, K: int, metric: int = L2, block: int = 512, shortlist: int = 32):
+    """Ground truth on whatever device the tensors live on (harness only; used at the 1M scale).
+
+    fp32 matrix products pick a shortlist of K + `shortlist` candidates per query, which is then
+    re-ranked by directly evaluated fp64 squared distances and ordered by (dist, id).
+    Returns (ids int64 [nq,K], keys float64 [nq,K]) as numpy arrays.
+    """
+    import torch
+    n = base_t.shape[0]
+    K = min(K, n)
+    kk = min(n, K + shortlist)
+    b = base_t
+    q = queries_t
+    if metric == COS:
+        b = b / b.norm(dim=1, keepdim=True).clamp_min(1e-30)
+        q = q / q.norm(dim=1, keepdim=True).clamp_min(1e-30)
+    bn = (b.double() ** 2).sum(1).float()
+    ids_out, keys_out = [], []
+    for s in range(0, q.shape[0], block):
+        qq = q[s:s + block]
+        d2 = bn[None, :] - 2.0 * (qq @ b.T)
+        cand = torch.topk(d2, kk, dim=1, largest=False).indices           # [blk, kk]
+        diff = b[cand].double() - qq.double()[:, None, :]
+        dd = (diff * diff).sum(-1)
+        # total order (dist, id): sort by id first (stable), then by distance (stable)
+        o1 = torch.argsort(cand, dim=1, stable=True)
+        cand, dd = torch.gather(cand, 1, o1), torch.gather(dd, 1, o1)
+        o2 = torch.argsort(dd, dim=1, stable=True)[:, :K]
+        ids_out.append(torch.gather(cand, 1, o2).cpu().numpy())
+        keys_out.append(torch.gather(dd, 1, o2).cpu().numpy())
+    ids = np.concatenate(ids_out).astype(np.int64)
+    keys = np.concatenate(keys_out)
+    return ids, keys_from(metric, keys)

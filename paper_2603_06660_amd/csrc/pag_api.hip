@@ -444,10 +444,12 @@ static int prepare(pag_index* ix, const float* Q, u64 nq, float* qrot, float* ta
 
 static u32 seen_log2_for(const pag_index* ix, u32 ef, u32 b) {
     if (ix->seen_log2) return ix->seen_log2;
-    // room for about twice the exact distances of a typical search (entries + a few per visited node)
+    // First level of the seen set: an LDS hash with room for about twice the exact distances of a
+    // short search (entries + a few per visited node).  It is capped at 2048 slots (8 KB): larger
+    // tables cost more in occupancy than the HBM bitmap behind it costs in extra loads.
     const u32 want = 2 * (b + 8 * std::max(ef, b));
-    u32 lg = 10;
-    while ((1u << lg) < want && lg < 13) ++lg;
+    u32 lg = 9;
+    while ((1u << lg) < want && lg < 11) ++lg;
     return lg;
 }
 

@@ -210,6 +210,8 @@ __global__ void __launch_bounds__(64) k_reverse(const float* __restrict__ vec, u
         if (id == PAG_EMPTY) {                                // a dropped neighbour leaves a clean slot
             ((float*)(rec + L.off_a))[lane] = 0.f;
             ((float*)(rec + L.off_c))[lane] = 0.f;
+            u32* cw = (u32*)(rec + L.off_codes) + (u32)lane * L.cw;
+            for (u32 k = 0; k < L.cw; ++k) cw[k] = 0u;
         }
     }
     const u32 nch = (u32)__popcll(changed);

@@ -99,15 +99,6 @@ struct Wave {
         s_hops = s_tests = s_passes = s_exact = s_rounds = s_rf = s_rt = s_spill = s_queries = 0;
     }
 
-    __device__ __forceinline__ bool seen(u32 id) const {
-        if (hash_contains(H, A.hlog, id)) return true;
-        if (n_spill) {
-            u32 w = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return (w >> (id & 31)) & 1u;
-        }
-        return false;
-    }
-
     // exact keys ||q - x_id||^2 (Alg. 2, "compute the distance") for the lanes in `mask`;
     // lane p receives the key of its own id.  Differences in fp32, squares summed in fp64,
     // one rounding to fp32 at the end.
@@ -321,10 +312,16 @@ struct Wave {
                         }
                     }
                 }
-                bool cand = id != PAG_EMPTY && id < A.n_limit;
-                if (cand) cand = !seen(id);
+                const bool in_graph = id != PAG_EMPTY && id < A.n_limit;
+                // seen-set lookup, HBM part first: the bitmap word is requested now and only consumed
+                // after the LDS probe and the table sums, so its latency overlaps with that work
+                u32 bm_word = 0;
+                if (n_spill && in_graph)
+                    bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                bool cand = in_graph;
+                if (cand) cand = !hash_contains(H, A.hlog, id);
                 // projection test: S = sum_l T[l][code_l] (increasing l), est = D_u + c - 2 a S
-                bool pass = cand;
+                float est = 0.f;
                 if (!(A.flags & PAG_FLAG_NO_PRT)) {
                     float S = 0.f;
                     if (cand) {
@@ -338,9 +335,11 @@ struct Wave {
                             }
                         }
                     }
-                    const float est = __builtin_fmaf(-2.0f * ea, S, Du + ec);
-                    pass = cand && (est < Dmax);
+                    est = __builtin_fmaf(-2.0f * ea, S, Du + ec);
                 }
+                cand = cand && !((bm_word >> (id & 31)) & 1u);
+                bool pass = cand;
+                if (!(A.flags & PAG_FLAG_NO_PRT)) pass = cand && (est < Dmax);
                 const u64 cmask = __ballot(cand);
                 const u64 pmask = __ballot(pass);
                 s_tests += (u32)__popcll(cmask);

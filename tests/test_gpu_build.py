@@ -1,0 +1,151 @@
+"""GPU index construction and online insertion (Alg. 1, Step 1; Sec. 4.1), through the C ABI.
+
+The batch-synchronous build does not produce the sequential build's graph, so it is judged the way
+the paper judges an index: recall against brute force.  What *is* checked element by element is
+everything derived from the graph: the rotated vectors, the per-edge inference information, and the
+search over the exported index (oracle and GPU walk the same arrays).
+"""
+import numpy as np
+import pytest
+
+import pag_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2603_06660_amd import PagIndex, load_library
+    load_library()
+    return PagIndex
+
+
+def _oracle_view(orc, ex):
+    return orc.OracleIndex(ex["vectors"], ex["adj"], ex["a"], ex["c"], ex["e2"], ex["codes"], ex["rotation"],
+                           ex["codebooks"], ex["entry"], metric=ex["metric"])
+
+
+def _check_graph(orc, ex, n):
+    adj = ex["adj"]
+    valid = adj != orc.EMPTY
+    assert adj[valid].max() < n
+    rows = np.arange(n)[:, None].repeat(adj.shape[1], 1)
+    assert not np.any(adj[valid] == rows[valid])
+    srt = np.sort(np.where(valid, adj, np.arange(adj.size, dtype=np.uint64).reshape(adj.shape) + (1 << 33)), axis=1)
+    assert not np.any(srt[:, 1:] == srt[:, :-1])          # no duplicate neighbours
+    assert valid.sum(1).min() >= 1
+
+
+@pytest.fixture(scope="module")
+def built(orc, cfg1_small):
+    PagIndex = _gpu()
+    w, base, q, gt, gtk = cfg1_small
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                         ef_construction=100, seed=21)
+    return gix, gix.export()
+
+
+def test_exported_index_is_consistent(orc, cfg1_small, built):
+    w, base, q, gt, gtk = cfg1_small
+    gix, ex = built
+    n = base.shape[0]
+    assert ex["vectors"].shape == base.shape and ex["entry"].tolist() == list(range(min(n, 1024)))
+    _check_graph(orc, ex, n)
+    rot = ex["rotation"].astype(np.float64)
+    assert np.allclose(rot @ rot.T, np.eye(w.d), atol=1e-6)
+    cb = ex["codebooks"].astype(np.float64)
+    assert np.allclose(np.linalg.norm(cb, axis=2), 1 / np.sqrt(w.P), atol=1e-6)
+    for l in (0, w.P - 1):
+        g = cb[l] @ cb[l].T * w.P
+        assert np.allclose(g[:8, :8], np.eye(8), atol=1e-5) and np.allclose(g[:8, 8:], -np.eye(8), atol=1e-5)
+    # rotated store = Q x (fp64 MFMA on the GPU, fp64 loop in the oracle)
+    ref = np.stack([orc.rotate(ex["rotation"], x) for x in base[:300]])
+    assert (ref == ex["vectors"][:300]).mean() >= 0.9999
+    # inference information of every stored edge, recomputed by the oracle from the exported vectors
+    oix = _oracle_view(orc, ex)
+    codes, a, c, e2 = oix.recompute_edge_info(0, n)
+    assert np.array_equal(codes, ex["codes"])
+    for got, want in ((ex["a"], a), (ex["c"], c), (ex["e2"], e2)):
+        assert np.allclose(got, want, rtol=2e-7, atol=0)
+        assert (got == want).mean() >= 0.999
+
+
+def test_recall_of_gpu_built_index(orc, cfg1_small, cfg1_oracle_index, built):
+    w, base, q, gt, gtk = cfg1_small
+    gix, ex = built
+    qd = torch.from_numpy(q).cuda()
+    rec = {}
+    for efS in (16, 32, 64, 128):
+        ids, _ = gix.search(qd, w.K, efS)
+        rec[efS] = wl.recall_at_k(ids.cpu().numpy(), gt)
+    assert rec[16] < rec[32] < rec[64] <= rec[128] + 0.002
+    assert rec[64] >= 0.95
+    # as good as the sequential build of the oracle, within noise
+    oi, _, _ = cfg1_oracle_index.search(q, w.K, 64)
+    assert rec[64] >= wl.recall_at_k(oi, gt) - 0.02
+
+
+def test_search_parity_on_exported_index(orc, cfg1_small, built):
+    w, base, q, gt, gtk = cfg1_small
+    gix, ex = built
+    oix = _oracle_view(orc, ex)
+    for efS in (32, 100):
+        gi, gd = gix.search(torch.from_numpy(q).cuda(), w.K, efS)
+        oi, od, _ = oix.search(q, w.K, efS)
+        gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+        assert (gi == oi).mean() >= 0.999
+        m = gi == oi
+        assert np.all(np.abs(gd[m] - od[m]) <= 1e-5 * od[m])
+        assert abs(wl.recall_at_k(gi, gt) - wl.recall_at_k(oi, gt)) <= 0.002
+
+
+def test_build_is_deterministic(orc, cfg1_small, built):
+    PagIndex = _gpu()
+    w, base, q, gt, gtk = cfg1_small
+    gix2 = PagIndex.build(torch.from_numpy(base).cuda(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                          ef_construction=100, seed=21)
+    ex2 = gix2.export()
+    _, ex = built
+    assert np.array_equal(np.sort(ex["adj"], axis=1), np.sort(ex2["adj"], axis=1))
+
+
+def test_online_insertion(orc, cfg1_small):
+    """Build on 2/3 of the data, insert the rest in two calls, search the whole set."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import PagError
+    w, base, q, gt, gtk = cfg1_small
+    n = base.shape[0]
+    bd = torch.from_numpy(base).cuda()
+    gix = PagIndex.build(bd[:2000].contiguous(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                         ef_construction=100, seed=22, capacity=n)
+    gix.insert(bd[2000:2600].contiguous())
+    gix.insert(bd[2600:].contiguous())
+    assert gix.describe()["n"] == n
+    with pytest.raises(PagError):
+        gix.insert(bd[:1].contiguous())                      # capacity exceeded
+    ids, dists = gix.search(torch.from_numpy(q).cuda(), w.K, 64)
+    ids = ids.cpu().numpy()
+    assert wl.recall_at_k(ids, gt) >= 0.95
+    assert (ids >= 2000).mean() > 0.2                        # inserted nodes are found
+    ex = gix.export()
+    _check_graph(orc, ex, n)
+    oix = _oracle_view(orc, ex)
+    oi, od, _ = oix.search(q, w.K, 64)
+    assert (ids == oi).mean() >= 0.999
+
+
+def test_ip_build_clustered(orc):
+    PagIndex = _gpu()
+    w = wl.workload(3, n=6000, nq=100)
+    w = w.__class__(**{**w.__dict__, "d": 256, "P": 16, "K": 10})
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    gt, _ = wl.brute_force(base, q, 10, wl.IP)
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric="ip", max_degree=w.deg, num_subspaces=16,
+                         ef_construction=128, seed=3)
+    ids, dists = gix.search(torch.from_numpy(q).cuda(), 10, 128)
+    assert wl.recall_at_k(ids.cpu().numpy(), gt) >= 0.9
+    ip = np.einsum("qkd,qd->qk", base[ids.cpu().numpy()].astype(np.float64), q.astype(np.float64))
+    assert np.allclose(dists.cpu().numpy(), 1.0 - ip, atol=3e-6)
