@@ -38,17 +38,22 @@ def algorithmic_bytes(c, d, K):
     return (c["queries"] * (4 * d + 8 * K) + c["hops"] * c["adj_record_bytes"] + c["exact"] * 4 * d)
 
 
-def read_traffic(tag):
-    """HBM bytes per search-kernel launch from the committed rocprofv3 counter summary, if it covers this run."""
+def read_traffic(tag, efS):
+    """HBM bytes per search-kernel launch from the committed rocprofv3 counter summary, if it covers this run
+    (same workload, same efS); otherwise None."""
     path = os.path.join(ROOT, "profiles", "search_kernel_%s_hbm_traffic.txt" % tag)
+    vals = {}
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("traffic_bytes_per_launch:"):
-                    return float(line.split(":")[1])
+                if line.startswith(("traffic_bytes_per_launch:", "efS:")):
+                    k, v = line.split(":")
+                    vals[k] = float(v)
     except OSError:
-        pass
-    return None
+        return None
+    if vals.get("efS") != float(efS):
+        return None
+    return vals.get("traffic_bytes_per_launch")
 
 
 def main():
@@ -164,7 +169,7 @@ def main():
     achieved = bytes_per_launch / (k_ms * 1e-3) / 1e9
     tag = "cfg%d" % w.cfg if (args.n is None and args.nq is None) else "custom"
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(tag),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(tag, efS),
                 "kernel": "pagk::k_search", "kernel_ms": round(k_ms, 4), "prepare_ms": round(float(np.mean(prep_ms)), 4),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch)}
 
