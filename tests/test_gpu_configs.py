@@ -1,0 +1,126 @@
+"""Search parity at the true shapes of the other workloads (d, K, degree, subspaces, metric, OOD
+queries, online insertion) on reduced n, and at the full size of the benchmark workload on a sample
+of the queries.  Index: built by the GPU library, exported, validated by the oracle, then searched
+by both sides."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import pag_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2603_06660_amd import PagIndex, load_library
+    load_library()
+    return PagIndex
+
+
+def _oracle_view(orc, ex):
+    return orc.OracleIndex(ex["vectors"], ex["adj"], ex["a"], ex["c"], ex["e2"], ex["codes"], ex["rotation"],
+                           ex["codebooks"], ex["entry"], metric=ex["metric"])
+
+
+def _parity(orc, gix, oix, q, K, efS, sample=None):
+    gi, gd = gix.search(torch.from_numpy(q).cuda(), K, efS)
+    gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+    sel = slice(None) if sample is None else sample
+    oi, od, oc = oix.search(q[sel], K, efS, threads=8)
+    gi_s, gd_s = gi[sel], gd[sel]
+    agree = (gi_s == oi).mean()
+    assert agree >= 0.999, agree
+    m = (gi_s == oi) & np.isfinite(od)
+    assert np.all(np.abs(gd_s[m] - od[m]) <= 1e-5 * np.abs(od[m]))
+    return gi, gd, oi
+
+
+def _check_edge_info(orc, oix, ex, nodes):
+    for lo in nodes:
+        codes, a, c, e2 = oix.recompute_edge_info(lo, lo + 64)
+        assert np.array_equal(codes, ex["codes"][lo:lo + 64])
+        assert np.allclose(a, ex["a"][lo:lo + 64], rtol=2e-7, atol=0)
+        assert np.allclose(c, ex["c"][lo:lo + 64], rtol=2e-7, atol=0)
+
+
+@pytest.mark.parametrize("cfg,n,nq,efC,efS", [(3, 20000, 200, 128, 256), (4, 20000, 200, 100, 128),
+                                              (5, 8000, 100, 100, 96)])
+def test_other_workload_shapes(orc, cfg, n, nq, efC, efS):
+    PagIndex = _gpu()
+    w = wl.workload(cfg, n=n, nq=nq)
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    metric = {0: "l2", 1: "ip", 2: "cos"}[w.metric]
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric=metric, max_degree=w.deg, num_subspaces=w.P,
+                         ef_construction=efC, seed=cfg)
+    ex = gix.export()
+    oix = _oracle_view(orc, ex)
+    _check_edge_info(orc, oix, ex, (0, n // 2, n - 64))
+    gt, _ = wl.brute_force(base, q, w.K, w.metric)
+    gi, gd, oi = _parity(orc, gix, oix, q, w.K, efS)
+    rg, ro = wl.recall_at_k(gi, gt), wl.recall_at_k(oi, gt)
+    assert abs(rg - ro) <= 0.002
+    assert rg >= 0.8, rg
+    if cfg == 4:                       # second retrieval size of that workload
+        _parity(orc, gix, oix, q, 50, 200)
+    # reported keys: 1 - <q, x> on unit vectors
+    qn = q / np.linalg.norm(q, axis=1, keepdims=True)
+    bn = base / np.linalg.norm(base, axis=1, keepdims=True)
+    ip = np.einsum("qkd,qd->qk", bn[gi].astype(np.float64), qn.astype(np.float64))
+    assert np.allclose(gd, 1.0 - ip, atol=5e-6)
+
+
+def test_online_insertion_rounds(orc):
+    """Workload 5's structure at reduced size: insertion batches interleaved with query batches."""
+    PagIndex = _gpu()
+    w = wl.workload(5, n=4000, nq=100)
+    w = dataclasses.replace(w, d=1024, P=32)
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric="ip", max_degree=w.deg, num_subspaces=w.P,
+                         ef_construction=100, seed=9, capacity=4000 + 3 * 500)
+    allv = base
+    for k in range(3):
+        x = wl.make(w, "insert%d" % k, n=500)
+        gix.insert(torch.from_numpy(x).cuda())
+        allv = np.concatenate([allv, x])
+        gt, _ = wl.brute_force(allv, q, w.K, w.metric)
+        ids, _ = gix.search(torch.from_numpy(q).cuda(), w.K, 128)
+        assert wl.recall_at_k(ids.cpu().numpy(), gt) >= 0.9
+    ex = gix.export()
+    assert ex["vectors"].shape[0] == 5500
+    _parity(orc, gix, _oracle_view(orc, ex), q, w.K, 128)
+
+
+def test_full_size_benchmark_workload(orc):
+    """n = 1,000,000 x 768, 10,000 queries in one call (the launch configuration the benchmark times);
+    the oracle searches the exported index for a sample of the queries."""
+    PagIndex = _gpu()
+    w = wl.workload(2)
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    base_d = torch.from_numpy(base).cuda()
+    gix = PagIndex.build(base_d, metric="ip", max_degree=w.deg, num_subspaces=w.P, ef_construction=200, seed=2603)
+    q_d = torch.from_numpy(q).cuda()
+    gt, _ = wl.brute_force_torch(base_d, q_d, w.K, w.metric)
+    del base_d
+    ex = gix.export()
+    oix = _oracle_view(orc, ex)
+    # exported store = Q x for sampled rows; inference information of sampled nodes
+    rows = np.arange(0, w.n, 50021)
+    ref = np.stack([orc.rotate(ex["rotation"], base[i]) for i in rows])
+    assert (ref == ex["vectors"][rows]).mean() >= 0.9999
+    _check_edge_info(orc, oix, ex, (0, 500_000, w.n - 64))
+    sample = np.arange(0, w.nq, 40)                      # 250 queries
+    for efS in (64, 512):
+        gi, gd, oi = _parity(orc, gix, oix, q, w.K, efS, sample=sample)
+        assert abs(wl.recall_at_k(gi[sample], gt[sample]) - wl.recall_at_k(oi, gt[sample])) <= 0.002
+        # property that holds for every query at any size: ascending keys, valid distinct ids
+        assert np.all(np.diff(gd, axis=1) >= 0) and gi.min() >= 0 and gi.max() < w.n
+        srt = np.sort(gi, axis=1)
+        assert not np.any(srt[:, 1:] == srt[:, :-1])
+    # sampled outputs checked one by one: the reported key is the true 1 - <q, x>
+    ip = np.einsum("qkd,qd->qk", base[gi[sample]].astype(np.float64), q[sample].astype(np.float64))
+    assert np.allclose(gd[sample], 1.0 - ip, atol=5e-6)
