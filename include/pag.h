@@ -106,6 +106,8 @@ typedef struct {
     double   last_search_kernel_ms; /* HIP-event time of the search kernel of the last pag_search */
     double   last_prepare_ms;       /* HIP-event time of rotation + projection tables of the last pag_search */
     double   last_build_ms;         /* wall time of the last pag_build / pag_insert */
+    uint64_t phase_cycles[6];       /* diagnostic: per-phase clock ticks of the search kernel, summed over waves;
+                                       all zero unless the library was compiled with -DPAG_PHASE_TIMERS */
 } pag_counters;
 
 /*

@@ -44,7 +44,7 @@ class _Counters(C.Structure):
                [(k, C.c_uint64) for k in ("queries", "hops", "tests", "passes", "exact", "rounds",
                                           "rf_overflow", "rt_overflow", "seen_spills")] + \
                [("last_search_kernel_ms", C.c_double), ("last_prepare_ms", C.c_double),
-                ("last_build_ms", C.c_double)]
+                ("last_build_ms", C.c_double), ("phase_cycles", C.c_uint64 * 6)]
 
 
 _lib = None
@@ -193,7 +193,9 @@ class PagIndex:
     def counters(self):
         c = _Counters(C.sizeof(_Counters))
         _check(load_library().pag_get_counters(self._h, C.byref(c)), "pag_get_counters")
-        return {k: getattr(c, k) for k, _ in c._fields_ if k != "struct_size"}
+        out = {k: getattr(c, k) for k, _ in c._fields_ if k not in ("struct_size", "phase_cycles")}
+        out["phase_cycles"] = list(c.phase_cycles)
+        return out
 
     def reset_counters(self):
         _check(load_library().pag_reset_counters(self._h), "pag_reset_counters")

@@ -22,7 +22,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-result", "-I", INCLUDE, "-I", CSRC,
-]
+] + os.environ.get("PAG_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def sources():

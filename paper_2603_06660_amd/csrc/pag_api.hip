@@ -399,6 +399,7 @@ extern "C" int pag_get_counters(const pag_index* ix, pag_counters* out) {
     out->last_search_kernel_ms = ix->last_search_ms;
     out->last_prepare_ms = ix->last_prepare_ms;
     out->last_build_ms = ix->last_build_ms;
+    for (int i = 0; i < 6; ++i) out->phase_cycles[i] = h[CTR_PHASE0 + i];
     return PAG_OK;
 }
 
@@ -442,15 +443,20 @@ static int prepare(pag_index* ix, const float* Q, u64 nq, float* qrot, float* ta
     return pag_launch_tables(ix->stream, qrot, nq, ix->L, ix->cb, tables);
 }
 
-static u32 seen_log2_for(const pag_index* ix, u32 ef, u32 b) {
-    if (ix->seen_log2) return ix->seen_log2;
-    // First level of the seen set: an LDS hash with room for about twice the exact distances of a
-    // short search (entries + a few per visited node).  It is capped at 2048 slots (8 KB): larger
-    // tables cost more in occupancy than the HBM bitmap behind it costs in extra loads.
-    const u32 want = 2 * (b + 8 * std::max(ef, b));
-    u32 lg = 9;
-    while ((1u << lg) < want && lg < 11) ++lg;
-    return lg;
+// Seen-set sizing.  First level: an exact LDS hash.  A search expected to compute at most ~1000
+// exact distances (entries + a few per visited node) gets a hash that holds all of them.  Longer
+// searches get a small hash for the early nodes, and behind it the per-wave HBM bitmap guarded by
+// an 8 KB LDS Bloom filter: large LDS tables cost more in occupancy than the bitmap costs in loads.
+static void seen_sizes_for(const pag_index* ix, u32 ef, u32 b, u32* hlog, u32* blog) {
+    const u32 expected = b + 8 * std::max(ef, b);
+    if (expected <= 1024) {
+        u32 lg = 9;
+        while ((1u << lg) < 2 * expected && lg < 11) ++lg;
+        *hlog = lg; *blog = 0;
+    } else {
+        *hlog = 9; *blog = 16;
+    }
+    if (ix->seen_log2) *hlog = ix->seen_log2;
 }
 
 // Fills the part of SearchArgs that depends only on the index and (b, ef); shared with indexing.
@@ -463,10 +469,10 @@ int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, 
     a->d = L.d; a->deg = L.deg; a->Ppad = L.Ppad; a->cw = L.cw; a->rec_bytes = L.rec_bytes;
     a->off_a = L.off_a; a->off_c = L.off_c; a->off_codes = L.off_codes;
     a->b = b; a->Rmax = std::max<u32>(1, (ef + b - 1) / b);
-    a->hlog = seen_log2_for(ix, ef, b);
+    seen_sizes_for(ix, ef, b, &a->hlog, &a->blog);
     a->flags = ix->flags;
     a->qcounter = ix->d_qcounter; a->counters = ix->d_counters;
-    *lds = (u32)pag_search_lds_bytes(L, b, a->hlog, a);
+    *lds = (u32)pag_search_lds_bytes(L, b, a->hlog, a->blog, a);
     int rc = pag_search_max_grid(ix, b, *lds, grid);
     if (rc) return rc;
     // per-wave spill bitmaps of the seen set: one bit per node, rounded to 16 bytes

@@ -32,7 +32,7 @@ void pag_set_error(const std::string& msg);
 // Device-side statistics, summed with atomics by every wave when it retires.
 enum {
     CTR_QUERIES = 0, CTR_HOPS, CTR_TESTS, CTR_PASSES, CTR_EXACT, CTR_ROUNDS, CTR_RF_OVER,
-    CTR_RT_OVER, CTR_SPILLS, CTR_COUNT
+    CTR_RT_OVER, CTR_SPILLS, CTR_PHASE0, CTR_PHASE1, CTR_PHASE2, CTR_PHASE3, CTR_PHASE4, CTR_PHASE5, CTR_COUNT
 };
 
 // Adjacency record of node u (one burst of whole 128-byte lines):
@@ -83,8 +83,9 @@ struct SearchArgs {
     u32 n_entry;
     u32 n_limit;             // only nodes < n_limit belong to the graph
     u32 d, deg, Ppad, cw, rec_bytes, off_a, off_c, off_codes;
-    u32 nq, K, b, Rmax, hlog, flags;
-    u32 off_hash, off_sa, off_sb, off_rf, off_rt;   // LDS offsets (bytes)
+    u32 nq, K, b, Rmax, hlog, blog, flags;   // hlog: log2 slots of the LDS hash; blog: log2 bits of the Bloom filter (0 = none)
+    u32 off_hash, off_bloom, off_sa, off_sb, off_rf, off_rt;   // LDS offsets (bytes)
+    u32 ring_mask;           // rings live in power-of-two buffers of >= 2b slots; only the last b pushes are valid
     long long* out_ids;      // [nq * K]       (search mode)
     float* out_dists;        // [nq * K]
     float out_scale;         // 1 for L2, 0.5 for IP / COS
@@ -99,7 +100,7 @@ struct SearchArgs {
 
 // kernels / launchers (defined in the .hip files)
 int pag_launch_search(const pag_index* ix, const SearchArgs& a, u32 lds_bytes, int* grid_out);
-int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, SearchArgs* a);
+int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, u32 blog, SearchArgs* a);
 int pag_search_max_grid(const pag_index* ix, u32 b, u32 lds_bytes, int* grid);
 
 int pag_launch_rotate(hipStream_t s, const float* X, u64 rows, u32 d, const float* rot, float* out);

@@ -27,13 +27,17 @@ static pag_search_fn pick(u32 d, u32 b) {
 static u32 align_up(u32 x, u32 a) { return (x + a - 1) / a * a; }
 
 // LDS carve-up of one wave; fills the offsets in `a` and returns the total.
-int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, SearchArgs* a) {
+int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, u32 blog, SearchArgs* a) {
     u32 off = align_up(L.Ppad * PAG_NCODE * 4, 16);
     a->off_hash = off; off += (4u << hlog);
+    a->off_bloom = off; off += blog ? (1u << blog) / 8 : 0;
     a->off_sa = off;   off += align_up(2 * b * 8, 16);
     a->off_sb = off;   off += align_up(2 * b * 8, 16);
-    a->off_rf = off;   off += align_up(b * 8, 16);
-    a->off_rt = off;   off += align_up(b * 8, 16);
+    u32 ring = 32;
+    while (ring < 2 * b) ring *= 2;
+    a->ring_mask = ring - 1;
+    a->off_rf = off;   off += ring * 8;
+    a->off_rt = off;   off += ring * 8;
     return (int)off;
 }
 

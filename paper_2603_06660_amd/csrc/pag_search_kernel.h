@@ -30,10 +30,52 @@ __device__ __forceinline__ u64 rdlane64(u64 v, int l) {
 }
 __device__ __forceinline__ u32 uniform(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
 
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double x) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// sum over each row of 16 lanes, result in every lane of the row: DPP quad_perm [1,0,3,2],
+// quad_perm [2,3,0,1], row_half_mirror, row_mirror (no LDS traffic)
+__device__ __forceinline__ double row16_sum(double x) {
+    x += dpp_move<0xB1>(x);
+    x += dpp_move<0x4E>(x);
+    x += dpp_move<0x141>(x);
+    x += dpp_move<0x140>(x);
     return x;
+}
+
+// Sums of G per-lane partials over the wave at once: the cross-row steps fold the G values
+// onto the four rows (each lane keeps the partials of "its" value and hands the others over),
+// the in-row steps are DPP.  Afterwards every lane of row r holds the total of value
+// r * G / 4 (G = 4), r / 2 (G = 2) or 0 (G = 1).
+template <int G>
+__device__ __forceinline__ double fold_sum(const double (&acc)[G], int lane) {
+    double k;
+    if constexpr (G == 4) {
+        const bool h32 = lane & 32, h16 = lane & 16;
+        double k0 = h32 ? acc[2] : acc[0], k1 = h32 ? acc[3] : acc[1];
+        const double s0 = h32 ? acc[0] : acc[2], s1 = h32 ? acc[1] : acc[3];
+        k0 += __shfl_xor(s0, 32, 64);
+        k1 += __shfl_xor(s1, 32, 64);
+        k = h16 ? k1 : k0;
+        const double sx = h16 ? k0 : k1;
+        k += __shfl_xor(sx, 16, 64);
+    } else if constexpr (G == 2) {
+        const bool h32 = lane & 32;
+        k = h32 ? acc[1] : acc[0];
+        const double sx = h32 ? acc[0] : acc[1];
+        k += __shfl_xor(sx, 32, 64);
+        k += __shfl_xor(k, 16, 64);
+    } else {
+        k = acc[0];
+        k += __shfl_xor(k, 32, 64);
+        k += __shfl_xor(k, 16, 64);
+    }
+    return row16_sum(k);
 }
 
 __device__ __forceinline__ u32 hash_slot(u32 id, u32 hlog) { return (id * 2654435761u) >> (32 - hlog); }
@@ -59,6 +101,18 @@ __device__ __forceinline__ void hash_insert(u32* H, u32 hlog, u32 id) {
     }
 }
 
+// Bloom filter over the ids that live in the HBM bitmap (two hash functions, LDS bit array):
+// "no" is definite, so most lookups of unseen nodes never touch HBM.
+__device__ __forceinline__ bool bloom_maybe(const u32* B, u32 blog, u32 id) {
+    const u32 h1 = (id * 0x9E3779B1u) >> (32 - blog), h2 = (id * 0x85EBCA77u) >> (32 - blog);
+    return ((B[h1 >> 5] >> (h1 & 31)) & (B[h2 >> 5] >> (h2 & 31)) & 1u) != 0;
+}
+__device__ __forceinline__ void bloom_set(u32* B, u32 blog, u32 id) {
+    const u32 h1 = (id * 0x9E3779B1u) >> (32 - blog), h2 = (id * 0x85EBCA77u) >> (32 - blog);
+    atomicOr(&B[h1 >> 5], 1u << (h1 & 31));
+    atomicOr(&B[h2 >> 5], 1u << (h2 & 31));
+}
+
 // dst[rank] = src[i], rank = number of smaller keys; keys are distinct.  n <= 4 * 64.
 __device__ __forceinline__ void rank_sort(const u64* src, u64* dst, u32 n, int lane) {
     for (u32 i = lane; i < n; i += 64) {
@@ -69,6 +123,20 @@ __device__ __forceinline__ void rank_sort(const u64* src, u64* dst, u32 n, int l
     }
 }
 
+// Optional per-phase timers (diagnostic builds only): every mark first drains all outstanding
+// memory operations, so the phases are timed as if they did not overlap.
+#ifdef PAG_PHASE_TIMERS
+#define PAG_MARK(i)                                                  \
+    do {                                                             \
+        __builtin_amdgcn_s_waitcnt(0);                               \
+        const u64 t__ = wall_clock64();                              \
+        s_phase[i] += t__ - t_last;                                  \
+        t_last = t__;                                                \
+    } while (0)
+#else
+#define PAG_MARK(i) do {} while (0)
+#endif
+
 template <int NQ, int NW>
 struct Wave {
     // constant for the kernel
@@ -76,6 +144,7 @@ struct Wave {
     const int lane;
     float* T;
     u32* H;
+    u32* BL;
     u64 *SA, *SB, *RF, *RT;
     u32* bitmap;
     // per query
@@ -83,65 +152,94 @@ struct Wave {
     u64 W[NW];
     u64 RL[NW];
     u32 nW, nRL;
-    u32 cntF, posF, cntT, posT;     // ring fill / next write position
+    u32 cntF, hdF, cntT, hdT;       // rings: valid entries (<= b) and total pushes; slot = push number & ring mask
     u32 n_hash, n_spill;
     // statistics (wave-uniform)
     u32 s_hops, s_tests, s_passes, s_exact, s_rounds, s_rf, s_rt, s_spill, s_queries;
+#ifdef PAG_PHASE_TIMERS
+    u64 s_phase[6];
+    u64 t_last;
+#endif
 
     __device__ Wave(const SearchArgs& a, unsigned char* smem, int ln) : A(a), lane(ln) {
         T = (float*)smem;
         H = (u32*)(smem + a.off_hash);
+        BL = (u32*)(smem + a.off_bloom);
         SA = (u64*)(smem + a.off_sa);
         SB = (u64*)(smem + a.off_sb);
         RF = (u64*)(smem + a.off_rf);
         RT = (u64*)(smem + a.off_rt);
         bitmap = a.bitmap + (u64)blockIdx.x * a.bitmap_words;
         s_hops = s_tests = s_passes = s_exact = s_rounds = s_rf = s_rt = s_spill = s_queries = 0;
+#ifdef PAG_PHASE_TIMERS
+        for (int i = 0; i < 6; ++i) s_phase[i] = 0;
+        t_last = wall_clock64();
+#endif
     }
 
     // exact keys ||q - x_id||^2 (Alg. 2, "compute the distance") for the lanes in `mask`;
     // lane p receives the key of its own id.  Differences in fp32, squares summed in fp64,
-    // one rounding to fp32 at the end.
+    // one rounding to fp32 at the end.  G vectors are in flight at a time: as soon as a slot's
+    // data has been folded into its partial sum the next vector is requested into that slot.
+    static constexpr int G = NQ <= 4 ? 4 : (NQ <= 8 ? 2 : 1);
+
+    __device__ __forceinline__ void load_vec(float4 (&v)[NQ], u32 id) const {
+        const float4* p = (const float4*)(A.vec + (u64)id * A.d);
+#pragma unroll
+        for (int c = 0; c < NQ; ++c) {
+            const u32 idx = c * 64 + lane;
+            if (c < NQ - 1 || idx * 4 < A.d) v[c] = p[idx];
+            else v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+
     __device__ __forceinline__ float exact_keys(u32 id_lane, u64 mask) {
-        constexpr int G = NQ <= 1 ? 8 : (NQ <= 4 ? 4 : (NQ <= 6 ? 2 : 1));
         float mine = 0.f;
-        const u32 d = A.d;
-        while (mask) {
+        float4 v[G][NQ];
+        u64 m_issue = mask, m_done = mask;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (m_issue) {
+                const int p = __ffsll((long long)m_issue) - 1;
+                m_issue &= m_issue - 1;
+                load_vec(v[g], rdlane(id_lane, p));
+            }
+        }
+        while (m_done) {
+            double acc[G];
             int pl[G];
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                if (mask) { pl[g] = __ffsll((long long)mask) - 1; mask &= mask - 1; }
-                else pl[g] = -1;
-            }
-            float4 v[G][NQ];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                if (pl[g] >= 0) {
-                    const u32 id = rdlane(id_lane, pl[g]);
-                    const float4* p = (const float4*)(A.vec + (u64)id * d);
+                acc[g] = 0.0;
+                pl[g] = -1;
+                if (m_done) {
+                    pl[g] = __ffsll((long long)m_done) - 1;
+                    m_done &= m_done - 1;
+                    double a = 0.0;
 #pragma unroll
                     for (int c = 0; c < NQ; ++c) {
-                        const u32 idx = c * 64 + lane;
-                        if (c < NQ - 1 || idx * 4 < d) v[g][c] = p[idx];
-                        else v[g][c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        const float dx = q[c].x - v[g][c].x, dy = q[c].y - v[g][c].y;
+                        const float dz = q[c].z - v[g][c].z, dw = q[c].w - v[g][c].w;
+                        a = __builtin_fma((double)dx, (double)dx, a);
+                        a = __builtin_fma((double)dy, (double)dy, a);
+                        a = __builtin_fma((double)dz, (double)dz, a);
+                        a = __builtin_fma((double)dw, (double)dw, a);
+                    }
+                    acc[g] = a;
+                    if (m_issue) {
+                        const int p = __ffsll((long long)m_issue) - 1;
+                        m_issue &= m_issue - 1;
+                        load_vec(v[g], rdlane(id_lane, p));
                     }
                 }
             }
+            const double tot = fold_sum<G>(acc, lane);
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 if (pl[g] >= 0) {
-                    double acc = 0.0;
-#pragma unroll
-                    for (int c = 0; c < NQ; ++c) {
-                        float dx = q[c].x - v[g][c].x, dy = q[c].y - v[g][c].y;
-                        float dz = q[c].z - v[g][c].z, dw = q[c].w - v[g][c].w;
-                        acc = __builtin_fma((double)dx, (double)dx, acc);
-                        acc = __builtin_fma((double)dy, (double)dy, acc);
-                        acc = __builtin_fma((double)dz, (double)dz, acc);
-                        acc = __builtin_fma((double)dw, (double)dw, acc);
-                    }
-                    acc = wave_sum(acc);
-                    if (lane == pl[g]) mine = (float)acc;
+                    const double t = __hiloint2double((int)rdlane((u32)__double2hiint(tot), g * (64 / G)),
+                                                      (int)rdlane((u32)__double2loint(tot), g * (64 / G)));
+                    if (lane == pl[g]) mine = (float)t;
                 }
             }
         }
@@ -154,13 +252,18 @@ struct Wave {
         if (np == 0) return;
         const u32 b = A.b;
         const bool pass = (mask >> lane) & 1ull;
+        PAG_MARK(2);
         const float dist = exact_keys(id_lane, mask);
+        PAG_MARK(3);
         s_exact += np;
         // seen set
         const bool spill = (n_hash + np) > (1u << (A.hlog - 1));
         if (pass) {
             if (!spill) hash_insert(H, A.hlog, id_lane);
-            else atomicOr(&bitmap[id_lane >> 5], 1u << (id_lane & 31));
+            else {
+                atomicOr(&bitmap[id_lane >> 5], 1u << (id_lane & 31));
+                if (A.blog) bloom_set(BL, A.blog, id_lane);
+            }
         }
         if (spill) { n_spill += np; s_spill += np; } else n_hash += np;
 
@@ -194,25 +297,25 @@ struct Wave {
             if (idx < nW) {
                 const u32 r = idx + cntW[s];
                 if (r < b) SA[r] = W[s];
-                else RT[(posT + (nW - 1 - idx)) % b] = W[s];       // largest first
+                else RT[(hdT + (nW - 1 - idx)) & A.ring_mask] = W[s];   // largest first
             }
         }
         if (pass) {
             if (rP < b) SA[rP] = pk;
             else {
                 const u32 oi = cP - n_ins;                          // smallest first
-                if (oi + b >= n_f) RF[(posF + oi) % b] = pk;        // older ones would be overwritten anyway
+                if (oi + b >= n_f) RF[(hdF + oi) & A.ring_mask] = pk;  // older ones would be overwritten anyway
             }
         }
         if (n_ej) {
             if (cntT + n_ej > b) s_rt += cntT + n_ej - b;
             cntT = cntT + n_ej < b ? cntT + n_ej : b;
-            posT = (posT + n_ej) % b;
+            hdT += n_ej;
         }
         if (n_f) {
             if (cntF + n_f > b) s_rf += cntF + n_f - b;
             cntF = cntF + n_f < b ? cntF + n_f : b;
-            posF = (posF + n_f) % b;
+            hdF += n_f;
         }
         __syncthreads();
 #pragma unroll
@@ -222,6 +325,7 @@ struct Wave {
         }
         nW = nW2;
         __syncthreads();
+        PAG_MARK(4);
     }
 
     __device__ __forceinline__ void run_query(u32 qi) {
@@ -238,10 +342,14 @@ struct Wave {
             for (u32 i = lane; i < A.Ppad * PAG_NCODE / 4; i += 64) ((float4*)T)[i] = tp[i];
             const uint4 e4 = make_uint4(PAG_EMPTY, PAG_EMPTY, PAG_EMPTY, PAG_EMPTY);
             for (u32 i = lane; i < (1u << A.hlog) / 4; i += 64) ((uint4*)H)[i] = e4;
+            if (A.blog) {
+                const uint4 z4 = make_uint4(0, 0, 0, 0);
+                for (u32 i = lane; i < (1u << A.blog) / 128; i += 64) ((uint4*)BL)[i] = z4;
+            }
 #pragma unroll
             for (int s = 0; s < NW; ++s) { W[s] = PAG_KEY_INVALID; RL[s] = PAG_KEY_INVALID; }
             nW = nRL = 0;
-            cntF = posF = cntT = posT = 0;
+            cntF = hdF = cntT = hdT = 0;
             n_hash = n_spill = 0;
             __syncthreads();
         }
@@ -274,6 +382,7 @@ struct Wave {
                     if (us < 0 && m) { us = s; ul = __ffsll((long long)m) - 1; }
                 }
                 if (us < 0) break;
+                PAG_MARK(5);
                 u64 ukey = 0;
 #pragma unroll
                 for (int s = 0; s < NW; ++s)
@@ -292,6 +401,7 @@ struct Wave {
                     for (int s = 0; s < NW; ++s)
                         if ((int)(wr >> 6) == s) Dmax = __uint_as_float(rdlane((u32)(W[s] >> 32), wr & 63));
                 }
+                PAG_MARK(0);
                 // adjacency record of u
                 const uint8_t* rec = A.rec + (u64)u * A.rec_bytes;
                 u32 id = PAG_EMPTY;
@@ -312,14 +422,16 @@ struct Wave {
                         }
                     }
                 }
+                PAG_MARK(1);
                 const bool in_graph = id != PAG_EMPTY && id < A.n_limit;
-                // seen-set lookup, HBM part first: the bitmap word is requested now and only consumed
-                // after the LDS probe and the table sums, so its latency overlaps with that work
-                u32 bm_word = 0;
-                if (n_spill && in_graph)
-                    bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // seen-set lookup: LDS hash, then (for ids that may live in the HBM bitmap according to
+                // the Bloom filter) the bitmap word, requested now and consumed only after the table
+                // sums so that its latency overlaps with them
                 bool cand = in_graph;
                 if (cand) cand = !hash_contains(H, A.hlog, id);
+                u32 bm_word = 0;
+                if (n_spill && cand && (A.blog == 0 || bloom_maybe(BL, A.blog, id)))
+                    bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 // projection test: S = sum_l T[l][code_l] (increasing l), est = D_u + c - 2 a S
                 float est = 0.f;
                 if (!(A.flags & PAG_FLAG_NO_PRT)) {
@@ -376,8 +488,8 @@ struct Wave {
                 __syncthreads();
             }
             {
-                for (u32 i = lane; i < cntF; i += 64) SA[i] = RF[i];
-                for (u32 i = lane; i < cntT; i += 64) SA[cntF + i] = RT[i];
+                for (u32 i = lane; i < cntF; i += 64) SA[i] = RF[(hdF - cntF + i) & A.ring_mask];
+                for (u32 i = lane; i < cntT; i += 64) SA[cntF + i] = RT[(hdT - cntT + i) & A.ring_mask];
                 __syncthreads();
                 const u32 n = cntF + cntT;
                 rank_sort(SA, SB, n, lane);
@@ -390,8 +502,8 @@ struct Wave {
                 }
                 const u32 rest = n - nW;                         // <= b; written worst first
                 for (u32 j = lane; j < rest; j += 64) RT[j] = SB[n - 1 - j];
-                cntT = rest; posT = rest % b;
-                cntF = 0; posF = 0;
+                cntT = rest; hdT = rest;
+                cntF = 0; hdF = 0;
                 __syncthreads();
             }
         }
@@ -435,6 +547,9 @@ struct Wave {
             atomicAdd(&A.counters[CTR_RF_OVER], (u64)s_rf);
             atomicAdd(&A.counters[CTR_RT_OVER], (u64)s_rt);
             atomicAdd(&A.counters[CTR_SPILLS], (u64)s_spill);
+#ifdef PAG_PHASE_TIMERS
+            for (int i = 0; i < 6; ++i) atomicAdd(&A.counters[CTR_PHASE0 + i], s_phase[i]);
+#endif
         }
     }
 };
