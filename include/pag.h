@@ -65,6 +65,7 @@ typedef struct {
 } pag_params;
 
 #define PAG_FLAG_NO_PRT 1u    /* ablation: skip the projection test, every unseen neighbour gets an exact distance */
+#define PAG_FLAG_NO_PES 2u    /* ablation: index without the PES candidate buffers H(v) (Eq. 5; Alg. 1's last loop) */
 
 /*
  * Flat host view of an index (Alg. 1 output: node set, edge set E, inference

@@ -14,7 +14,8 @@
  *     argmax that picks r*_il);
  *   - the search of Alg. 2 / Sec. 3.3 with the working set W, the rings R_F and
  *     R_T and the list R_L;
- *   - RobustPrune, Eq. 1 (alpha = 1), and the per-node body of Alg. 1 (Step 1).
+ *   - RobustPrune, Eq. 1 (alpha = 1), and Alg. 1: Step 1 per node, the PES screening of
+ *     Step 2 and the verification of the buffered candidates (Step 3).
  *
  * Precision contract (decisions are taken in the same precision on both sides):
  *   rotated vectors, projection tables, exact distance keys and the stored
@@ -285,12 +286,16 @@ static float w_max(const ent *W, uint32_t nW, uint32_t b) {
  *           ORC_NO_PRT: the projection test is skipped (every unseen neighbour
  *              gets an exact distance).
  * n_nodes limits the graph to ids < n_nodes (used while indexing).
+ * H (optional, indexing): PES candidate buffer of the searched point v (Alg. 1): every expanded
+ * node u that survives the screening of Eq. 5 is recorded, the closest capH of them are kept,
+ * ascending by (dist, id).
  * Output: out[0..*n_out) sorted by (dist, id).  scratch->seen is left cleared,
  * scratch->seen_list[0..n_seen) holds every node whose exact distance was computed.
  */
 void orc_search_core(const orc_index *ix, uint64_t n_nodes, const float *q, const float *T,
                      uint32_t ef, uint32_t b, uint32_t rl_cap, int flags, orc_scratch *sc,
-                     ent *out, uint32_t *n_out, orc_counters *ctr) {
+                     ent *out, uint32_t *n_out, orc_counters *ctr, ent *H, uint32_t *nH,
+                     uint32_t capH) {
     const uint32_t d = ix->d, P = ix->P, deg = ix->deg;
     uint32_t Rmax = (ef + b - 1) / b;
     if (Rmax == 0) Rmax = 1;
@@ -329,6 +334,30 @@ void orc_search_core(const orc_index *ix, uint64_t n_nodes, const float *q, cons
             const float Du = W[ui].dist;
             float Dmax = w_max(W, nW, b);
             uint32_t np = 0;
+            if (H) {
+                /* PES screening (Eq. 5): max_i (cos theta_i / cos beta_i - delta_i) < 0.  In estimate form
+                 * (multiply through by 2 ||v-u|| ||w_i-u|| > 0): every est_i = D_u + c_i - 2 a_i S_i exceeds
+                 * D_u, i.e. no out-neighbour of u is estimated to lie closer to v than u does. */
+                int survives = 1;
+                for (uint32_t i = 0; i < deg && survives; ++i) {
+                    uint64_t s = (uint64_t)u * deg + i;
+                    uint32_t w = ix->adj[s];
+                    if (w == ORC_EMPTY || w >= n_nodes) continue;
+                    float est = orc_est32(Du, ix->a[s], ix->c[s], orc_S32(P, T, ix->codes + s * P));
+                    if (!(est > Du)) survives = 0;
+                }
+                if (survives) {
+                    ent e = { Du, u, 0 };
+                    uint32_t pos = *nH;
+                    while (pos > 0 && ent_less(&e, &H[pos - 1])) pos--;
+                    if (pos < capH) {
+                        uint32_t last = *nH < capH ? *nH : capH - 1;
+                        for (uint32_t k = last; k > pos; --k) H[k] = H[k - 1];
+                        H[pos] = e;
+                        if (*nH < capH) (*nH)++;
+                    }
+                }
+            }
             for (uint32_t i = 0; i < deg; ++i) {
                 uint64_t s = (uint64_t)u * deg + i;
                 uint32_t w = ix->adj[s];
@@ -402,7 +431,7 @@ int orc_search_batch(const orc_index *ix, int metric, const float *Q, uint64_t n
         orc_rotate(d, ix->rot, q, qr);
         orc_table(d, P, ix->cb, qr, T, NULL);
         uint32_t n_out = 0;
-        orc_search_core(ix, ix->n, qr, T, efS, b, K, flags, &sc, out, &n_out, &local);
+        orc_search_core(ix, ix->n, qr, T, efS, b, K, flags, &sc, out, &n_out, &local, NULL, NULL, 0);
         for (uint32_t k = 0; k < K; ++k) {
             if (k < n_out) {
                 ids[i * K + k] = (int64_t)out[k].id;
@@ -536,8 +565,37 @@ void orc_reverse_edge(orc_index *ix, uint32_t u, uint32_t v, float duv) {
  * vectors of all nodes; adjacency arrays of the new nodes must be ORC_EMPTY.
  * With n_start == 0 the first min(efC, 100) nodes are linked to their nearest
  * min(deg, .) among themselves ("select b initial nodes, connect them").
+ * use_pes: Step 2 and Step 3 as well -- every insertion fills its buffer H(v) (capacity deg =
+ * 2M) through the PES screening, and after all insertions the buffered candidates are verified.
  */
-int orc_build(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, orc_counters *ctr) {
+/*
+ * Verification of one PES candidate u -> v (Alg. 1, last loop): the RobustPrune condition of
+ * Eq. 1 is evaluated exactly; an accepted edge is added only to a free out-degree slot of u,
+ * existing edges are kept unchanged.  Returns 1 if the edge was added.
+ */
+int orc_pes_edge(orc_index *ix, uint32_t u, uint32_t v, float duv) {
+    const uint32_t d = ix->d, deg = ix->deg;
+    const float *vv = ix->vec + (uint64_t)v * d;
+    int free_slot = -1;
+    for (uint32_t i = 0; i < deg; ++i) {
+        uint64_t s = (uint64_t)u * deg + i;
+        uint32_t w = ix->adj[s];
+        if (w == ORC_EMPTY) { if (free_slot < 0) free_slot = (int)i; continue; }
+        if (w == v) return 0;
+    }
+    if (free_slot < 0) return 0;
+    for (uint32_t i = 0; i < deg; ++i) {
+        uint64_t s = (uint64_t)u * deg + i;
+        uint32_t w = ix->adj[s];
+        if (w == ORC_EMPTY) continue;
+        if (ix->e2[s] <= duv && orc_key(d, ix->vec + (uint64_t)w * d, vv) <= duv) return 0;
+    }
+    write_edge(ix, u, (uint32_t)free_slot, v);
+    return 1;
+}
+
+int orc_build(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, orc_counters *ctr, int use_pes,
+              uint64_t *pes_added) {
     const uint32_t d = ix->d, P = ix->P, deg = ix->deg;
     uint32_t b = efC < 100 ? efC : 100;
     if (b == 0 || d % P != 0) return -1;
@@ -550,6 +608,8 @@ int orc_build(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, orc
     float *ckey = (float *)malloc(sizeof(float) * ((size_t)efC + b));
     uint32_t *kept = (uint32_t *)malloc(sizeof(uint32_t) * deg);
     float *kkey = (float *)malloc(sizeof(float) * deg);
+    ent *Hall = use_pes ? (ent *)malloc(sizeof(ent) * (size_t)(n_end - n_start) * deg) : NULL;
+    uint32_t *nHall = use_pes ? (uint32_t *)calloc(n_end - n_start, sizeof(uint32_t)) : NULL;
     uint64_t v0 = n_start;
     if (n_start == 0) {
         uint64_t n_init = n_end < b ? n_end : b;
@@ -571,13 +631,24 @@ int orc_build(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, orc
         const float *vv = ix->vec + v * d;
         orc_table(d, P, ix->cb, vv, T, NULL);
         uint32_t n_out = 0;
-        orc_search_core(ix, v, vv, T, efC, b, efC, 0, &sc, rl, &n_out, &local);
+        ent *H = use_pes ? Hall + (v - n_start) * deg : NULL;
+        orc_search_core(ix, v, vv, T, efC, b, efC, 0, &sc, rl, &n_out, &local, H,
+                        use_pes ? &nHall[v - n_start] : NULL, deg);
         for (uint32_t i = 0; i < n_out; ++i) { cand[i] = rl[i].id; ckey[i] = rl[i].dist; }
         uint32_t nk = orc_robust_prune(ix, n_out, cand, ckey, deg, kept, kkey);
         for (uint32_t i = 0; i < nk; ++i) write_edge(ix, (uint32_t)v, i, kept[i]);
         for (uint32_t i = 0; i < nk; ++i) orc_reverse_edge(ix, kept[i], (uint32_t)v, kkey[i]);
     }
+    uint64_t added = 0;
+    if (use_pes)
+        for (uint64_t v = v0; v < n_end; ++v) {
+            const ent *H = Hall + (v - n_start) * deg;
+            for (uint32_t i = 0; i < nHall[v - n_start]; ++i)
+                added += (uint64_t)orc_pes_edge(ix, H[i].id, (uint32_t)v, H[i].dist);
+        }
+    if (pes_added) *pes_added = added;
     if (ctr) *ctr = local;
+    free(Hall); free(nHall);
     free(sc.seen); free(sc.seen_list); free(T); free(rl); free(cand); free(ckey); free(kept); free(kkey);
     return 0;
 }

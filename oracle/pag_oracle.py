@@ -209,8 +209,8 @@ class OracleIndex:
 
     # -- construction ---------------------------------------------------
     @classmethod
-    def build(cls, data, metric=L2, deg=32, P=16, efC=100, seed=1, rot=None, cb=None):
-        """Alg. 1, Step 1, sequentially over `data` (raw float32 [n, d])."""
+    def build(cls, data, metric=L2, deg=32, P=16, efC=100, seed=1, rot=None, cb=None, pes=True):
+        """Alg. 1 sequentially over `data` (raw float32 [n, d]); pes=False leaves out Steps 2 and 3."""
         data = _f32(data)
         n, d = data.shape
         rot = make_transform(d, seed) if rot is None else _f32(rot)
@@ -230,9 +230,12 @@ class OracleIndex:
                    np.arange(min(n, 1024), dtype=np.uint32), metric)
         ctr = Counters()
         st = self._struct()
-        rc = L.orc_build(C.byref(st), C.c_uint32(efC), C.c_uint64(0), C.c_uint64(n), C.byref(ctr))
+        added = C.c_uint64(0)
+        rc = L.orc_build(C.byref(st), C.c_uint32(efC), C.c_uint64(0), C.c_uint64(n), C.byref(ctr),
+                         C.c_int(1 if pes else 0), C.byref(added))
         assert rc == 0
         self.build_counters = ctr.as_dict()
+        self.pes_edges_added = int(added.value)
         return self
 
     # -- search ---------------------------------------------------------

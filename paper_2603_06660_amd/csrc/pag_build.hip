@@ -82,6 +82,7 @@ __global__ void __launch_bounds__(64) k_init_clique(const float* __restrict__ ve
 __global__ void __launch_bounds__(64) k_prune_new(const float* __restrict__ vec, uint8_t* __restrict__ recs,
                                                   pag_layout L, u32 node0, u32 m, const u64* __restrict__ cand,
                                                   const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
+                                                  const u64* __restrict__ pes,
                                                   u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sv = (float*)smem;                  // [d] candidate vector
@@ -128,6 +129,23 @@ __global__ void __launch_bounds__(64) k_prune_new(const float* __restrict__ vec,
         const u64 o = (u64)vi * L.deg + lane;
         rev_keys[o] = my_id == PAG_EMPTY ? PAG_KEY_INVALID : (((u64)my_id << 32) | my_key);
         rev_vals[o] = v;
+        if (pes) {
+            // PES candidates u -> v (Alg. 1, H(v)): pairs flagged in bit 31 of the distance word (a
+            // non-negative float never sets it), so that they sort behind the ordinary reverse edges
+            // of the same target and are only granted free slots.  Nodes already chosen as
+            // out-neighbours of v have their ordinary pair.
+            const u64 hk = pes[(u64)vi * L.deg + lane];
+            u64 pk = PAG_KEY_INVALID;
+            if (hk != PAG_KEY_INVALID) {
+                const u32 u = (u32)(hk & 0xFFFFFFFFull) >> 1;
+                bool dup = false;
+                for (u32 s = 0; s < nk; ++s) dup = dup || kept[s] == u;
+                if (!dup) pk = ((u64)u << 32) | 0x80000000ull | (hk >> 32);
+            }
+            const u64 o2 = (u64)m * L.deg + o;
+            rev_keys[o2] = pk;
+            rev_vals[o2] = v;
+        }
     }
 }
 
@@ -137,6 +155,8 @@ __global__ void __launch_bounds__(64) k_prune_new(const float* __restrict__ vec,
 //   refuse if some w in N_out(u) has ||w-u||^2 <= duv and ||w-v||^2 <= duv;
 //   else take a free slot; if the list is full, drop the neighbours farther than v that v now
 //   occludes (||v-f||^2 <= ||f-u||^2), or failing that the farthest of N_out(u) + {v}.
+// Pairs that come from the PES buffers H(v) (flag in bit 31 of the distance word) pass the same
+// Eq. 1 check but are only ever given a free slot.
 // Every slot that received a new neighbour is appended to `edges` for the inference-information pass.
 __global__ void __launch_bounds__(64) k_reverse(const float* __restrict__ vec, uint8_t* __restrict__ recs,
                                                 float* __restrict__ e2, pag_layout L,
@@ -160,9 +180,12 @@ __global__ void __launch_bounds__(64) k_reverse(const float* __restrict__ vec, u
         const u64 k = keys[i];
         if (k == PAG_KEY_INVALID || (u32)(k >> 32) != u) break;
         const u32 v = vals[i];
-        const float duv = __uint_as_float((u32)(k & 0xFFFFFFFFull));
+        const bool from_pes = (k >> 31) & 1ull;
+        const float duv = __uint_as_float((u32)(k & 0x7FFFFFFFull));
         const bool valid = (u32)lane < L.deg && id != PAG_EMPTY;
         if (__ballot(valid && id == v)) continue;
+        // PES candidates are only added to available out-degree slots (Alg. 1, last loop)
+        if (from_pes && __ballot((u32)lane < L.deg && id == PAG_EMPTY) == 0ull) continue;
         stage(vec, L.d, v, sv, lane);
         __syncthreads();
         // lane s gets ||w_s - v||^2
@@ -228,12 +251,12 @@ __global__ void __launch_bounds__(64) k_reverse(const float* __restrict__ vec, u
 }
 
 struct BuildWs {
-    u64* cand = nullptr; u32* cand_cnt = nullptr;
+    u64* cand = nullptr; u32* cand_cnt = nullptr; u64* pes = nullptr;
     u64 *rk_in = nullptr, *rk_out = nullptr; u32 *rv_in = nullptr, *rv_out = nullptr;
     u32* edges = nullptr; u32* n_edges = nullptr;
     void* sort_tmp = nullptr; size_t sort_bytes = 0;
     ~BuildWs() {
-        void* p[] = { cand, cand_cnt, rk_in, rk_out, rv_in, rv_out, edges, n_edges, sort_tmp };
+        void* p[] = { cand, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, sort_tmp };
         for (void* x : p) if (x) (void)hipFree(x);
     }
 };
@@ -276,7 +299,9 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     BuildWs ws;
     PAG_ALLOC(ws.cand, max_batch * cand_cap * 8);
     PAG_ALLOC(ws.cand_cnt, max_batch * 4);
-    const u64 max_pairs = max_batch * L.deg;
+    const bool use_pes = !(ix->flags & PAG_FLAG_NO_PES);
+    if (use_pes) PAG_ALLOC(ws.pes, max_batch * L.deg * 8);
+    const u64 max_pairs = max_batch * L.deg * (use_pes ? 2 : 1);
     PAG_ALLOC(ws.rk_in, max_pairs * 8);
     PAG_ALLOC(ws.rk_out, max_pairs * 8);
     PAG_ALLOC(ws.rv_in, max_pairs * 4);
@@ -314,17 +339,18 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         if ((rc = pag_search_common(ix, b, ix->efC, pos, &a, &lds, &grid))) return rc;
         a.qrot = qrot; a.tables = ix->ws_tab; a.nq = (u32)m; a.K = b;
         a.cand = ws.cand; a.cand_cnt = ws.cand_cnt; a.cand_cap = cand_cap;
+        a.pes = ws.pes;
         if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
         if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
         // 3. RobustPrune -> N_out(v), reverse pairs
         {
             const u32 plds = L.d * 4 + cand_cap * 8 + L.deg * 4;
             hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, ix->vec, ix->rec, L, (u32)pos, (u32)m,
-                               ws.cand, ws.cand_cnt, cand_cap, ix->efC, ws.rk_in, ws.rv_in);
+                               ws.cand, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
             PAG_HIP(hipGetLastError());
         }
         // 4. group reverse pairs by target
-        const u32 n_pairs = (u32)(m * L.deg);
+        const u32 n_pairs = (u32)(m * L.deg * (use_pes ? 2 : 1));
         PAG_HIP(hipcub::DeviceRadixSort::SortPairs(ws.sort_tmp, ws.sort_bytes, ws.rk_in, ws.rk_out, ws.rv_in, ws.rv_out,
                                                    (int)n_pairs, 0, 64, s));
         // 5. apply them

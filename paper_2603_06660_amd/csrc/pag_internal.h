@@ -92,6 +92,7 @@ struct SearchArgs {
     u64* cand;               // [nq * cand_cap] keys of R_L (indexing mode), sorted per round
     u32* cand_cnt;           // [nq]
     u32 cand_cap;
+    u64* pes;                // [nq * deg] indexing mode: PES buffer H(v), ascending keys, PAG_KEY_INVALID = empty; null = off
     u32* qcounter;
     u64* counters;
     u32* bitmap;             // [grid * bitmap_words]

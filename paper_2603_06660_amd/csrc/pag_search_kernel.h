@@ -154,6 +154,7 @@ struct Wave {
     u32 nW, nRL;
     u32 cntF, hdF, cntT, hdT;       // rings: valid entries (<= b) and total pushes; slot = push number & ring mask
     u32 n_hash, n_spill;
+    u64 Hk;                         // indexing: PES buffer H(v), lane i = i-th closest surviving node (Alg. 1)
     // statistics (wave-uniform)
     u32 s_hops, s_tests, s_passes, s_exact, s_rounds, s_rf, s_rt, s_spill, s_queries;
 #ifdef PAG_PHASE_TIMERS
@@ -351,6 +352,7 @@ struct Wave {
             nW = nRL = 0;
             cntF = hdF = cntT = hdT = 0;
             n_hash = n_spill = 0;
+            Hk = PAG_KEY_INVALID;
             __syncthreads();
         }
         s_queries++;
@@ -434,9 +436,10 @@ struct Wave {
                     bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 // projection test: S = sum_l T[l][code_l] (increasing l), est = D_u + c - 2 a S
                 float est = 0.f;
+                const bool want_pes = A.pes != nullptr;   // indexing: every neighbour's estimate feeds Eq. 5
                 if (!(A.flags & PAG_FLAG_NO_PRT)) {
                     float S = 0.f;
-                    if (cand) {
+                    if (cand || (want_pes && in_graph)) {
 #pragma unroll
                         for (int k = 0; k < PAG_MAX_CW; ++k) {
                             if ((u32)k < A.cw) {
@@ -452,6 +455,18 @@ struct Wave {
                 cand = cand && !((bm_word >> (id & 31)) & 1u);
                 bool pass = cand;
                 if (!(A.flags & PAG_FLAG_NO_PRT)) pass = cand && (est < Dmax);
+                if (want_pes) {
+                    // PES screening (Eq. 5): max_i (cos theta_i / cos beta_i - delta_i) < 0 for all neighbours
+                    // <=> every estimate est_i exceeds D_u, i.e. no neighbour of u looks closer to v than
+                    // u itself.  Then u -> v is a candidate edge; H(v) keeps the closest `deg` such nodes.
+                    if (__ballot(in_graph && !(est > Du)) == 0ull) {
+                        const u64 key = (ukey & ~1ull);
+                        const u32 pos = (u32)__popcll(__ballot(Hk < key));
+                        const u64 up = __shfl_up(Hk, 1, 64);
+                        if ((u32)lane == pos) Hk = key;
+                        else if ((u32)lane > pos) Hk = up;
+                    }
+                }
                 const u64 cmask = __ballot(cand);
                 const u64 pmask = __ballot(pass);
                 s_tests += (u32)__popcll(cmask);
@@ -511,6 +526,7 @@ struct Wave {
         // ---- output ----
         if (A.cand) {
             if (lane == 0) A.cand_cnt[qi] = n_cand;
+            if (A.pes && (u32)lane < deg) A.pes[(u64)qi * deg + lane] = Hk;
         } else {
 #pragma unroll
             for (int s = 0; s < NW; ++s) {

@@ -149,3 +149,22 @@ def test_ip_build_clustered(orc):
     assert wl.recall_at_k(ids.cpu().numpy(), gt) >= 0.9
     ip = np.einsum("qkd,qd->qk", base[ids.cpu().numpy()].astype(np.float64), q.astype(np.float64))
     assert np.allclose(dists.cpu().numpy(), 1.0 - ip, atol=3e-6)
+
+
+def test_pes_switch(orc, cfg1_small, built):
+    """Index with and without the PES buffers (Eq. 5; Alg. 1's last loop): both valid, PES only adds edges."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_NO_PES
+    w, base, q, gt, gtk = cfg1_small
+    gix0 = PagIndex.build(torch.from_numpy(base).cuda(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                          ef_construction=100, seed=21, flags=FLAG_NO_PES)
+    ex0 = gix0.export()
+    _, ex1 = built
+    _check_graph(orc, ex0, base.shape[0])
+    d0 = (ex0["adj"] != orc.EMPTY).sum()
+    d1 = (ex1["adj"] != orc.EMPTY).sum()
+    assert d1 > d0
+    qd = torch.from_numpy(q).cuda()
+    r0 = wl.recall_at_k(gix0.search(qd, w.K, 64)[0].cpu().numpy(), gt)
+    r1 = wl.recall_at_k(built[0].search(qd, w.K, 64)[0].cpu().numpy(), gt)
+    assert r1 >= r0 - 0.01 and r0 >= 0.94

@@ -241,3 +241,24 @@ def test_routing_test_success_probability(orc):
         trials += 1
         hits += s["prt"] >= 0
     assert hits / trials >= 0.5 - 3 * 0.5 / sqrt(trials)
+
+
+def test_pes_sign_equals_estimate_comparison(orc):
+    """Eq. 5 term for one neighbour, cos(theta)/cos(beta) - delta with delta = ||w-u|| / (2 ||v-u||):
+    negative  <=>  the estimate of ||v-w||^2 exceeds ||v-u||^2 (w is not an estimated witness).
+    Also delta itself: cos(alpha) > delta  <=>  ||w-v|| < ||v-u|| (law of cosines, Sec. 3.4)."""
+    rng = np.random.default_rng(21)
+    checked = 0
+    for _ in range(300):
+        d, P = [(8, 2), (16, 4), (32, 4), (24, 3)][int(rng.integers(4))]
+        cb, u, w, v = _random_case(rng, orc, d, P)
+        v = (u + float(rng.uniform(0.3, 2.0)) * (v - u)).astype(np.float32)
+        s = orc.stats(cb, u, w, v, 1.0)
+        du = orc.sqdist64(v, u)
+        if s["cos_beta"] < 1e-3 or abs(s["pes_term"]) < 1e-9:
+            continue
+        assert (s["pes_term"] < 0) == (s["est"] > du)
+        if abs(s["cos_alpha"] - s["delta"]) > 1e-6:
+            assert (s["cos_alpha"] > s["delta"]) == (orc.sqdist64(v, w) < du)
+        checked += 1
+    assert checked > 250

@@ -208,3 +208,33 @@ def test_sequential_build_graph_is_valid(orc, cfg1_small, cfg1_oracle_index):
     codes, a, c, e2 = ix.recompute_edge_info(0, 200)
     assert np.array_equal(codes, ix.codes[:200])
     assert np.array_equal(a, ix.a[:200]) and np.array_equal(c, ix.c[:200]) and np.array_equal(e2, ix.e2[:200])
+
+
+def test_pes_adds_edges_only_to_free_slots(orc, cfg1_small):
+    """Alg. 1, last loop: verified PES candidates fill available out-degree slots; existing edges are
+    kept unchanged.  The insertion searches do not depend on the buffers H(v), so the graph without
+    PES must be contained, slot by slot, in the graph with PES."""
+    w, base, q, gt, gtk = cfg1_small
+    kw = dict(deg=w.deg, P=w.P, efC=64, seed=13)
+    plain = orc.OracleIndex.build(base[:1500], w.metric, pes=False, **kw)
+    full = orc.OracleIndex.build(base[:1500], w.metric, pes=True, **kw)
+    used = plain.adj != orc.EMPTY
+    assert np.array_equal(full.adj[used], plain.adj[used])
+    new = (full.adj != orc.EMPTY) & ~used
+    assert new.sum() == full.pes_edges_added > 0
+    # every added edge u -> v passes Eq. 1 against the neighbours u had before it:
+    # no earlier w with ||w-u|| <= ||v-u|| and ||w-v|| <= ||v-u||
+    us, slots = np.nonzero(new)
+    for u, s in list(zip(us, slots))[:200]:
+        v = full.adj[u, s]
+        duv = orc.key(full.vec[u], full.vec[v])
+        for t in range(w.deg):
+            x = plain.adj[u, t]
+            if x == orc.EMPTY:
+                continue
+            assert not (orc.key(full.vec[x], full.vec[u]) <= duv and orc.key(full.vec[x], full.vec[v]) <= duv)
+    # and the index is at least as good
+    gt15, _ = wl.brute_force(base[:1500], q, w.K)
+    r0 = wl.recall_at_k(plain.search(q, w.K, 32)[0], gt15)
+    r1 = wl.recall_at_k(full.search(q, w.K, 32)[0], gt15)
+    assert r1 >= r0 - 0.01
