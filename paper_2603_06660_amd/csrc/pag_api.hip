@@ -4,6 +4,7 @@
 #include <chrono>
 #include <cmath>
 #include <cstring>
+#include <functional>
 #include <thread>
 #include <vector>
 
@@ -42,33 +43,41 @@ struct Rng {
     }
 };
 
-// Orthonormalise the columns of the dim x dim Gaussian matrix g (column-major) in place.
+// Orthonormalise the columns of the dim x dim Gaussian matrix g (column-major) in place:
+// classical Gram-Schmidt with one re-orthogonalisation pass, both inner loops split over threads.
 void orthonormalise(std::vector<double>& g, uint32_t dim, unsigned threads) {
     std::vector<double> proj(dim);
+    auto parallel = [&](uint32_t count, const std::function<void(uint32_t, uint32_t)>& fn) {
+        if (threads <= 1 || count < 256) { fn(0, count); return; }
+        std::vector<std::thread> th;
+        for (unsigned t = 0; t < threads; ++t)
+            th.emplace_back(fn, (uint32_t)((uint64_t)count * t / threads), (uint32_t)((uint64_t)count * (t + 1) / threads));
+        for (auto& x : th) x.join();
+    };
     for (uint32_t j = 0; j < dim; ++j) {
         double* aj = &g[(size_t)j * dim];
-        for (int pass = 0; pass < 2; ++pass) {
-            auto dots = [&](uint32_t lo, uint32_t hi) {
+        for (int pass = 0; pass < 2 && j > 0; ++pass) {
+            parallel(j, [&](uint32_t lo, uint32_t hi) {
                 for (uint32_t i = lo; i < hi; ++i) {
                     const double* qi = &g[(size_t)i * dim];
                     double s = 0.0;
                     for (uint32_t k = 0; k < dim; ++k) s += qi[k] * aj[k];
                     proj[i] = s;
                 }
-            };
-            if (threads > 1 && j >= 256) {
-                std::vector<std::thread> th;
-                for (unsigned t = 0; t < threads; ++t)
-                    th.emplace_back(dots, (uint32_t)((uint64_t)j * t / threads), (uint32_t)((uint64_t)j * (t + 1) / threads));
-                for (auto& x : th) x.join();
-            } else {
-                dots(0, j);
-            }
-            for (uint32_t i = 0; i < j; ++i) {
-                const double* qi = &g[(size_t)i * dim];
-                const double p = proj[i];
-                for (uint32_t k = 0; k < dim; ++k) aj[k] -= p * qi[k];
-            }
+            });
+            parallel(j >= 256 ? dim : 0, [&](uint32_t lo, uint32_t hi) {
+                for (uint32_t i = 0; i < j; ++i) {
+                    const double* qi = &g[(size_t)i * dim];
+                    const double p = proj[i];
+                    for (uint32_t k = lo; k < hi; ++k) aj[k] -= p * qi[k];
+                }
+            });
+            if (j < 256)
+                for (uint32_t i = 0; i < j; ++i) {
+                    const double* qi = &g[(size_t)i * dim];
+                    const double p = proj[i];
+                    for (uint32_t k = 0; k < dim; ++k) aj[k] -= p * qi[k];
+                }
         }
         double nrm = 0.0;
         for (uint32_t k = 0; k < dim; ++k) nrm += aj[k] * aj[k];

@@ -574,6 +574,9 @@ struct Wave {
 // so long and short searches balance themselves; the loop ends for every wave once the counter
 // passes nq.
 template <int NQ, int NW>
+#ifdef PAG_WAVES_PER_EU
+__attribute__((amdgpu_waves_per_eu(PAG_WAVES_PER_EU, 8)))
+#endif
 __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x;
