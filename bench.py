@@ -32,10 +32,10 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(c, d, K):
+def algorithmic_bytes(c, d, K, vec_bytes=4):
     """Bytes the method itself must move (Sec. 4.2's terms): per query the query vector and the
     results, per expanded node its adjacency record, per exact distance one base vector."""
-    return (c["queries"] * (4 * d + 8 * K) + c["hops"] * c["adj_record_bytes"] + c["exact"] * 4 * d)
+    return (c["queries"] * (4 * d + 8 * K) + c["hops"] * c["adj_record_bytes"] + c["exact"] * vec_bytes * d)
 
 
 def read_traffic(tag, efS):
@@ -122,6 +122,8 @@ def main():
     ap.add_argument("--efs", type=int, default=0, help="skip the sweep and time this efS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--fp16-vectors", action="store_true",
+                    help="keep the base vectors as 16-bit floats (the paper's payload); NOT the headline configuration")
     ap.add_argument("--rounds", type=int, default=10, help="cfg 5: insertion rounds")
     ap.add_argument("--insert-batch", type=int, default=50000, help="cfg 5: vectors per insertion round")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -156,8 +158,10 @@ def main():
     del base
 
     t0 = time.time()
+    from paper_2603_06660_amd import FLAG_FP16_VECTORS
+    vec_bytes = 2 if args.fp16_vectors else 4
     ix = PagIndex.build(base_d, metric=metric, max_degree=w.deg, num_subspaces=w.P, ef_construction=args.efc,
-                        seed=2603)
+                        seed=2603, flags=FLAG_FP16_VECTORS if args.fp16_vectors else 0)
     build_s = time.time() - t0
     log("pag_build: %.2f s (%.0f vectors/s)" % (build_s, w.n / build_s))
 
@@ -223,10 +227,10 @@ def main():
     c = ix.counters()
     ms_per_step = 1e3 * elapsed / args.steps
     qps = w.nq * args.steps / elapsed
-    bytes_per_launch = algorithmic_bytes(c, w.d, w.K) / args.steps
+    bytes_per_launch = algorithmic_bytes(c, w.d, w.K, vec_bytes) / args.steps
     k_ms = float(np.mean(kernel_ms))
     achieved = bytes_per_launch / (k_ms * 1e-3) / 1e9
-    tag = "cfg%d" % w.cfg if (args.n is None and args.nq is None) else "custom"
+    tag = "cfg%d" % w.cfg if (args.n is None and args.nq is None and not args.fp16_vectors) else "custom"
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(tag, efS),
                 "kernel": "pagk::k_search", "kernel_ms": round(k_ms, 4), "prepare_ms": round(float(np.mean(prep_ms)), 4),
@@ -259,7 +263,7 @@ def main():
         "metric": "batched QPS at recall@%d>=0.95 (1 GPU)" % w.K, "value": round(qps, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-        "data": "synthetic",
+        "data": "synthetic" + (" (base vectors stored as 16-bit floats)" if args.fp16_vectors else ""),
         "config": {"workload": "cfg%d %s: n=%d d=%d nq=%d K=%d deg=%d P=%d efC=%d" %
                                (w.cfg, w.name, w.n, w.d, w.nq, w.K, w.deg, w.P, args.efc),
                    "efS": efS, "efS_within_configured_grid": bool(efS <= max(w.efs_grid)),

@@ -65,6 +65,9 @@ typedef struct {
 } pag_params;
 
 #define PAG_FLAG_NO_PRT 1u    /* ablation: skip the projection test, every unseen neighbour gets an exact distance */
+#define PAG_FLAG_FP16_VECTORS 4u /* keep the rotated base vectors as 16-bit floats (the paper's payload, Sec. 4.2): halves the
+                                   bytes per exact distance; the index then *is* the rounded data, and all arithmetic on it
+                                   stays fp32/fp64.  Needs d % 8 == 0.  Build / import time only. */
 #define PAG_FLAG_NO_PES 2u    /* ablation: index without the PES candidate buffers H(v) (Eq. 5; Alg. 1's last loop) */
 
 /*
@@ -80,7 +83,8 @@ typedef struct {
     uint32_t num_subspaces;   /* P */
     uint32_t max_degree;      /* deg */
     uint32_t n_entry;
-    float*    vectors;   /* host [n*d]        base vectors after normalisation (COS) and rotation by Q */
+    float*    vectors;   /* host [n*d]        base vectors after normalisation (COS) and rotation by Q (and rounding
+                                              to 16-bit floats with PAG_FLAG_FP16_VECTORS), as fp32 */
     uint32_t* adj;       /* host [n*deg]      out-neighbour ids; 0xFFFFFFFF = free slot */
     float*    a;         /* host [n*deg]      a_i = ||w_i-u|| / cos(beta_i)            (Sec. 3.1) */
     float*    c;         /* host [n*deg]      c_i = ||w_i-u||^2 + 2 a_i sum_l <u_l, r*_il>  (stored offsets, Appendix C) */

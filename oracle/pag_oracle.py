@@ -209,8 +209,10 @@ class OracleIndex:
 
     # -- construction ---------------------------------------------------
     @classmethod
-    def build(cls, data, metric=L2, deg=32, P=16, efC=100, seed=1, rot=None, cb=None, pes=True):
-        """Alg. 1 sequentially over `data` (raw float32 [n, d]); pes=False leaves out Steps 2 and 3."""
+    def build(cls, data, metric=L2, deg=32, P=16, efC=100, seed=1, rot=None, cb=None, pes=True, vec_f16=False):
+        """Alg. 1 sequentially over `data` (raw float32 [n, d]); pes=False leaves out Steps 2 and 3.
+        vec_f16: the rotated vectors are rounded to 16-bit floats (the paper's payload, Sec. 4.2) and the
+        index is built over those values."""
         data = _f32(data)
         n, d = data.shape
         rot = make_transform(d, seed) if rot is None else _f32(rot)
@@ -224,6 +226,8 @@ class OracleIndex:
                 L.orc_normalise(C.c_uint32(d), _p(x), _p(tmp))
                 x = tmp
             L.orc_rotate(C.c_uint32(d), _p(rot), _p(x), _p(vec[i]))
+        if vec_f16:
+            vec = vec.astype(np.float16).astype(np.float32)
         self = cls(vec, np.full((n, deg), EMPTY, np.uint32), np.zeros((n, deg), np.float32),
                    np.zeros((n, deg), np.float32), np.zeros((n, deg), np.float32),
                    np.zeros((n, deg, P), np.uint8), rot, cb,

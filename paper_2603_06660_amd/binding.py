@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libpag_hip.so")
 L2, IP, COS = 0, 1, 2
 FLAG_NO_PRT = 1
 FLAG_NO_PES = 2
+FLAG_FP16_VECTORS = 4
 _METRICS = {"l2": L2, "ip": IP, "cos": COS, "cosine": COS, L2: L2, IP: IP, COS: COS}
 
 EXPORTED_SYMBOLS = (

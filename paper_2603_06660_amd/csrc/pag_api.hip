@@ -174,7 +174,11 @@ struct DeviceGuard {
 // allocate the HBM-resident parts of an index for `capacity` nodes
 int alloc_index(pag_index* ix) {
     int rc;
-    if ((rc = dev_alloc(&ix->vec, ix->capacity * ix->L.d))) return rc;
+    {
+        uint8_t* raw = nullptr;
+        if ((rc = dev_alloc(&raw, ix->capacity * ix->L.d * pag_vec_elem(ix)))) return rc;
+        ix->vec = raw;
+    }
     if ((rc = dev_alloc(&ix->rec, ix->capacity * ix->L.rec_bytes))) return rc;
     if ((rc = dev_alloc(&ix->e2, ix->capacity * ix->L.deg))) return rc;
     if ((rc = dev_alloc(&ix->rot, (u64)ix->L.d * ix->L.d))) return rc;
@@ -196,7 +200,8 @@ pag_index* new_index(const pag_params* p, uint32_t d) {
     ix->efC = p->ef_construction;
     ix->search_b = p->search_b;
     ix->subbatch = p->insert_subbatch;
-    ix->flags = p->flags;
+    ix->flags = p->flags & ~PAG_FLAG_FP16_VECTORS;
+    ix->vec_half = (p->flags & PAG_FLAG_FP16_VECTORS) ? 1u : 0u;
     ix->seed = p->seed;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, ix->device) == hipSuccess) ix->num_cu = prop.multiProcessorCount;
@@ -215,16 +220,29 @@ int set_entry_list(pag_index* ix) {
     return PAG_OK;
 }
 
-// normalise (COS) + rotate `rows` raw vectors X (dev) into dst (dev)
-int ingest(pag_index* ix, const float* X, u64 rows, float* dst) {
-    const float* src = X;
+// normalise (COS) + rotate `rows` raw vectors X (dev) into rows [row0, row0 + rows) of the store
+int ingest(pag_index* ix, const float* X, u64 rows, u64 row0) {
+    const u32 d = ix->L.d;
     int rc;
-    if (ix->metric == PAG_COS) {
-        if ((rc = ensure_ws(&ix->ws_norm, &ix->ws_norm_cap, rows * ix->L.d))) return rc;
-        if ((rc = pag_launch_normalise(ix->stream, X, rows, ix->L.d, ix->ws_norm))) return rc;
-        src = ix->ws_norm;
+    const u64 slab = 1ull << 18;
+    for (u64 s0 = 0; s0 < rows; s0 += slab) {
+        const u64 cnt = std::min<u64>(slab, rows - s0);
+        const float* src = X + s0 * d;
+        if (ix->metric == PAG_COS) {
+            if ((rc = ensure_ws(&ix->ws_norm, &ix->ws_norm_cap, cnt * d))) return rc;
+            if ((rc = pag_launch_normalise(ix->stream, src, cnt, d, ix->ws_norm))) return rc;
+            src = ix->ws_norm;
+        }
+        if (!ix->vec_half) {
+            if ((rc = pag_launch_rotate(ix->stream, src, cnt, d, ix->rot, (float*)ix->vec + (row0 + s0) * d))) return rc;
+        } else {
+            // fp32 result of the rotation first, then one rounding to the 16-bit store
+            if ((rc = ensure_ws(&ix->ws_qrot, &ix->ws_qrot_cap, cnt * d))) return rc;
+            if ((rc = pag_launch_rotate(ix->stream, src, cnt, d, ix->rot, ix->ws_qrot))) return rc;
+            if ((rc = pag_launch_convert(ix->stream, ix->ws_qrot, 0, (__half*)ix->vec + (row0 + s0) * d, 1, cnt * d))) return rc;
+        }
     }
-    return pag_launch_rotate(ix->stream, src, rows, ix->L.d, ix->rot, dst);
+    return PAG_OK;
 }
 
 }  // namespace
@@ -252,8 +270,8 @@ extern "C" int pag_build(const float* D, uint64_t n, uint32_t d, const pag_param
     PAG_CHECK(n < (1ull << 31), PAG_EUNSUPPORTED, "n must be below 2^31");
     pag_layout L;
     if ((rc = make_layout(d, params->num_subspaces, params->max_degree, &L))) return rc;
-    const u32 b_idx = std::min<u32>(params->ef_construction, 100);
-    (void)b_idx;
+    PAG_CHECK(!(params->flags & PAG_FLAG_FP16_VECTORS) || d % 8 == 0, PAG_EUNSUPPORTED,
+              "PAG_FLAG_FP16_VECTORS needs d % 8 == 0");
     pag_index* ix = new_index(params, d);
     ix->L = L;
     ix->capacity = std::max<u64>(params->capacity, n);
@@ -268,7 +286,7 @@ extern "C" int pag_build(const float* D, uint64_t n, uint32_t d, const pag_param
     if (e == hipSuccess) e = hipMemsetAsync(ix->rec, 0xFF, ix->capacity * L.rec_bytes, ix->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ix->stream);
     if (e != hipSuccess) { pag_free(ix); pag_set_error(std::string("pag_build upload: ") + hipGetErrorString(e)); return PAG_EHIP; }
-    if ((rc = ingest(ix, D, n, ix->vec))) { pag_free(ix); return rc; }
+    if ((rc = ingest(ix, D, n, 0))) { pag_free(ix); return rc; }
     ix->n = 0;
     if ((rc = pag_build_range(ix, 0, n))) { pag_free(ix); return rc; }
     ix->n = n;
@@ -286,7 +304,7 @@ extern "C" int pag_insert(pag_index* ix, const float* X, uint64_t m) {
     DeviceGuard g(ix->device);
     const auto t0 = std::chrono::steady_clock::now();
     int rc;
-    if ((rc = ingest(ix, X, m, ix->vec + ix->n * ix->L.d))) return rc;
+    if ((rc = ingest(ix, X, m, ix->n))) return rc;
     if ((rc = pag_build_range(ix, ix->n, ix->n + m))) return rc;
     ix->n += m;
     if ((rc = set_entry_list(ix))) return rc;
@@ -311,7 +329,26 @@ extern "C" int pag_export(const pag_index* ix, pag_arrays* out) {
     const pag_layout& L = ix->L;
     const u64 n = ix->n;
     PAG_HIP(hipStreamSynchronize(ix->stream));
-    PAG_HIP(hipMemcpy(out->vectors, ix->vec, n * L.d * 4, hipMemcpyDeviceToHost));
+    if (!ix->vec_half) {
+        PAG_HIP(hipMemcpy(out->vectors, ix->vec, n * L.d * 4, hipMemcpyDeviceToHost));
+    } else {
+        const u64 vslab = 1ull << 18;
+        float* tmp = nullptr;
+        int rc2 = dev_alloc(&tmp, std::min<u64>(vslab, n) * L.d);
+        if (rc2) return rc2;
+        for (u64 s0 = 0; s0 < n; s0 += vslab) {
+            const u64 cnt = std::min<u64>(vslab, n - s0);
+            rc2 = pag_launch_convert(ix->stream, (const __half*)ix->vec + s0 * L.d, 1, tmp, 0, cnt * L.d);
+            hipError_t e2 = rc2 ? hipSuccess : hipStreamSynchronize(ix->stream);
+            if (!rc2 && e2 == hipSuccess) e2 = hipMemcpy(out->vectors + s0 * L.d, tmp, cnt * L.d * 4, hipMemcpyDeviceToHost);
+            if (rc2 || e2 != hipSuccess) {
+                (void)hipFree(tmp);
+                if (!rc2) { pag_set_error(std::string("pag_export: ") + hipGetErrorString(e2)); return PAG_EHIP; }
+                return rc2;
+            }
+        }
+        (void)hipFree(tmp);
+    }
     PAG_HIP(hipMemcpy(out->e2, ix->e2, n * L.deg * 4, hipMemcpyDeviceToHost));
     PAG_HIP(hipMemcpy(out->rotation, ix->rot, (u64)L.d * L.d * 4, hipMemcpyDeviceToHost));
     PAG_HIP(hipMemcpy(out->codebooks, ix->cb, (u64)L.P * PAG_NCODE * L.dsub * 4, hipMemcpyDeviceToHost));
@@ -356,6 +393,8 @@ extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_in
         PAG_CHECK(in->adj[i] == PAG_EMPTY || in->adj[i] < n, PAG_EINVAL, "pag_import: neighbour id out of range");
     for (u32 i = 0; i < in->n_entry; ++i) PAG_CHECK(in->entry[i] < n, PAG_EINVAL, "pag_import: entry id out of range");
     for (u64 i = 0; i < n * L.deg * L.P; ++i) PAG_CHECK(in->codes[i] < PAG_NCODE, PAG_EINVAL, "pag_import: code above 15");
+    PAG_CHECK(!(params->flags & PAG_FLAG_FP16_VECTORS) || in->d % 8 == 0, PAG_EUNSUPPORTED,
+              "PAG_FLAG_FP16_VECTORS needs d % 8 == 0");
     pag_index* ix = new_index(params, in->d);
     ix->metric = in->metric;
     ix->L = L;
@@ -365,7 +404,18 @@ extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_in
     hipError_t e;
     if ((e = hipMemsetAsync(ix->rec, 0xFF, ix->capacity * L.rec_bytes, ix->stream)) != hipSuccess) return fail(e);
     if ((e = hipStreamSynchronize(ix->stream)) != hipSuccess) return fail(e);
-    if ((e = hipMemcpy(ix->vec, in->vectors, n * L.d * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+    if (!ix->vec_half) {
+        if ((e = hipMemcpy(ix->vec, in->vectors, n * L.d * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+    } else {
+        const u64 vslab = 1ull << 18;
+        if ((rc = ensure_ws(&ix->ws_qrot, &ix->ws_qrot_cap, std::min<u64>(vslab, n) * L.d))) { pag_free(ix); return rc; }
+        for (u64 s0 = 0; s0 < n; s0 += vslab) {
+            const u64 cnt = std::min<u64>(vslab, n - s0);
+            if ((e = hipMemcpy(ix->ws_qrot, in->vectors + s0 * L.d, cnt * L.d * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
+            if ((rc = pag_launch_convert(ix->stream, ix->ws_qrot, 0, (__half*)ix->vec + s0 * L.d, 1, cnt * L.d))) { pag_free(ix); return rc; }
+            if ((e = hipStreamSynchronize(ix->stream)) != hipSuccess) return fail(e);
+        }
+    }
     if ((e = hipMemcpy(ix->e2, in->e2, n * L.deg * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
     if ((e = hipMemcpy(ix->rot, in->rotation, (u64)L.d * L.d * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
     if ((e = hipMemcpy(ix->cb, in->codebooks, (u64)L.P * PAG_NCODE * L.dsub * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
@@ -425,7 +475,7 @@ extern "C" int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t
     PAG_CHECK(ix, PAG_EINVAL, "null argument");
     PAG_CHECK(search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 128 is not built");
     ix->search_b = search_b;
-    ix->flags = flags;
+    ix->flags = (ix->flags & PAG_FLAG_NO_PES) | (flags & PAG_FLAG_NO_PRT);   // index-time bits stay as built
     return PAG_OK;
 }
 

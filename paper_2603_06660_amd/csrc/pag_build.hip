@@ -26,12 +26,11 @@ __device__ __forceinline__ double wave_sum(double x) {
 }
 
 // squared distance between the vector staged in LDS and row `id`, all lanes get the result
-__device__ __forceinline__ float dist_lds(const float* __restrict__ vec, u32 d, const float* s, u32 id, int lane) {
-    const float4* x = (const float4*)(vec + (u64)id * d);
+__device__ __forceinline__ float dist_lds(const pag_vecs& V, u32 d, const float* s, u32 id, int lane) {
     const float4* q = (const float4*)s;
     double acc = 0.0;
     for (u32 c = lane; c < d / 4; c += 64) {
-        const float4 a = q[c], b = x[c];
+        const float4 a = q[c], b = pag_vload4(V, id, c);
         const float dx = a.x - b.x, dy = a.y - b.y, dz = a.z - b.z, dw = a.w - b.w;
         acc = __builtin_fma((double)dx, (double)dx, acc);
         acc = __builtin_fma((double)dy, (double)dy, acc);
@@ -41,13 +40,12 @@ __device__ __forceinline__ float dist_lds(const float* __restrict__ vec, u32 d, 
     return (float)wave_sum(acc);
 }
 
-__device__ __forceinline__ void stage(const float* __restrict__ vec, u32 d, u32 id, float* s, int lane) {
-    const float4* x = (const float4*)(vec + (u64)id * d);
-    for (u32 c = lane; c < d / 4; c += 64) ((float4*)s)[c] = x[c];
+__device__ __forceinline__ void stage(const pag_vecs& V, u32 d, u32 id, float* s, int lane) {
+    for (u32 c = lane; c < d / 4; c += 64) ((float4*)s)[c] = pag_vload4(V, id, c);
 }
 
 // ---- initial nodes: each of the first n_init nodes is linked to its nearest min(deg, n_init-1) peers ----
-__global__ void __launch_bounds__(64) k_init_clique(const float* __restrict__ vec, uint8_t* __restrict__ recs,
+__global__ void __launch_bounds__(64) k_init_clique(pag_vecs vec, uint8_t* __restrict__ recs,
                                                     pag_layout L, u32 n_init) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sv = (float*)smem;                       // [d]
@@ -79,7 +77,7 @@ __global__ void __launch_bounds__(64) k_init_clique(const float* __restrict__ ve
 // across rounds.  Sorted ascending, cut to efC, then scanned: a candidate is kept unless an
 // already kept s has ||s - c|| <= ||v - c||.  Writes N_out(v) into v's record and one reverse
 // pair per kept neighbour: key = target << 32 | dist bits, value = v.
-__global__ void __launch_bounds__(64) k_prune_new(const float* __restrict__ vec, uint8_t* __restrict__ recs,
+__global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restrict__ recs,
                                                   pag_layout L, u32 node0, u32 m, const u64* __restrict__ cand,
                                                   const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
                                                   const u64* __restrict__ pes,
@@ -158,7 +156,7 @@ __global__ void __launch_bounds__(64) k_prune_new(const float* __restrict__ vec,
 // Pairs that come from the PES buffers H(v) (flag in bit 31 of the distance word) pass the same
 // Eq. 1 check but are only ever given a free slot.
 // Every slot that received a new neighbour is appended to `edges` for the inference-information pass.
-__global__ void __launch_bounds__(64) k_reverse(const float* __restrict__ vec, uint8_t* __restrict__ recs,
+__global__ void __launch_bounds__(64) k_reverse(pag_vecs vec, uint8_t* __restrict__ recs,
                                                 float* __restrict__ e2, pag_layout L,
                                                 const u64* __restrict__ keys, const u32* __restrict__ vals,
                                                 u32 n_pairs, u32* __restrict__ edges, u32* __restrict__ n_edges) {
@@ -282,7 +280,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         const u32 n_init = (u32)std::min<u64>(n_end, b);
         if (n_init > 1) {
             const u32 lds = L.d * 4 + 2 * n_init * 8;
-            hipLaunchKernelGGL(k_init_clique, dim3(n_init), dim3(64), lds, s, ix->vec, ix->rec, L, n_init);
+            hipLaunchKernelGGL(k_init_clique, dim3(n_init), dim3(64), lds, s, pag_vecs_of(ix), ix->rec, L, n_init);
             PAG_HIP(hipGetLastError());
             if ((rc = pag_launch_edge_info_nodes(s, ix, 0, n_init))) return rc;
         }
@@ -311,6 +309,12 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     PAG_HIP(hipcub::DeviceRadixSort::SortPairs(nullptr, ws.sort_bytes, ws.rk_in, ws.rk_out, ws.rv_in, ws.rv_out,
                                                (int)max_pairs, 0, 64, s));
     PAG_ALLOC(ws.sort_tmp, ws.sort_bytes);
+    if (ix->vec_half && ix->ws_qrot_cap < max_batch * L.d) {
+        if (ix->ws_qrot) (void)hipFree(ix->ws_qrot);
+        ix->ws_qrot = nullptr; ix->ws_qrot_cap = 0;
+        PAG_ALLOC(ix->ws_qrot, max_batch * L.d * 4);
+        ix->ws_qrot_cap = max_batch * L.d;
+    }
     {   // table workspace for the largest batch
         const u64 need = max_batch * L.Ppad * PAG_NCODE;
         if (ix->ws_tab_cap < need) {
@@ -329,7 +333,12 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         u64 m = std::min<u64>(n_end - pos, max_batch);
         m = std::min<u64>(m, std::max<u64>(1, pos / 2));
         // 1. projection tables of the new nodes (they are their own queries, already rotated)
-        const float* qrot = ix->vec + pos * L.d;
+        // the new nodes are their own queries; a 16-bit store is widened into the query workspace
+        const float* qrot = (const float*)ix->vec + pos * L.d;
+        if (ix->vec_half) {
+            if ((rc = pag_launch_convert(s, (const __half*)ix->vec + pos * L.d, 1, ix->ws_qrot, 0, m * L.d))) return rc;
+            qrot = ix->ws_qrot;
+        }
         if ((rc = pag_launch_tables(s, qrot, m, L, ix->cb, ix->ws_tab))) return rc;
         // 2. PRT-TFB search of the graph of nodes [0, pos)
         SearchArgs a;
@@ -345,7 +354,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         // 3. RobustPrune -> N_out(v), reverse pairs
         {
             const u32 plds = L.d * 4 + cand_cap * 8 + L.deg * 4;
-            hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, ix->vec, ix->rec, L, (u32)pos, (u32)m,
+            hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, (u32)pos, (u32)m,
                                ws.cand, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
             PAG_HIP(hipGetLastError());
         }
@@ -355,7 +364,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
                                                    (int)n_pairs, 0, 64, s));
         // 5. apply them
         if ((rc = pag_launch_zero_u32(s, ws.n_edges, 1))) return rc;
-        hipLaunchKernelGGL(k_reverse, dim3(n_pairs), dim3(64), L.d * 4, s, ix->vec, ix->rec, ix->e2, L, ws.rk_out,
+        hipLaunchKernelGGL(k_reverse, dim3(n_pairs), dim3(64), L.d * 4, s, pag_vecs_of(ix), ix->rec, ix->e2, L, ws.rk_out,
                            ws.rv_out, n_pairs, ws.edges, ws.n_edges);
         PAG_HIP(hipGetLastError());
         // 6. inference information of the new forward edges and of every changed reverse slot

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 
 #include <string>
@@ -46,6 +47,30 @@ struct pag_layout {
     u32 off_a, off_c, off_codes;
 };
 
+// Row-major vector store: fp32 elements, or 16-bit floats (the paper's own payload, Sec. 4.2).
+// A 16-bit store holds values that are exactly representable, so every kernel widens them to fp32
+// and then computes exactly as it would on an fp32 store holding those values.
+struct pag_vecs {
+    const void* base;
+    u32 d;
+    u32 half;   // 0: float, 1: __half
+};
+
+__device__ __forceinline__ float4 pag_vload4(const pag_vecs& V, u64 row, u32 c4) {   // elements [4*c4, 4*c4+4)
+    if (V.half) {
+        const uint2 raw = *(const uint2*)((const __half*)V.base + row * V.d + 4 * (u64)c4);
+        const __half2 lo = *(const __half2*)&raw.x, hi = *(const __half2*)&raw.y;
+        const float2 a = __half22float2(lo), b = __half22float2(hi);
+        return make_float4(a.x, a.y, b.x, b.y);
+    }
+    return ((const float4*)((const float*)V.base + row * V.d))[c4];
+}
+
+__device__ __forceinline__ float pag_vload1(const pag_vecs& V, u64 row, u32 k) {
+    if (V.half) return __half2float(((const __half*)V.base)[row * V.d + k]);
+    return ((const float*)V.base)[row * V.d + k];
+}
+
 struct pag_index {
     int device;
     hipStream_t stream;
@@ -55,7 +80,8 @@ struct pag_index {
     u32 efC, search_b, subbatch, flags, seen_log2;
     u64 seed;
     // HBM-resident index
-    float* vec;      // [capacity * d]   rotated vectors
+    void* vec;       // [capacity * d]   rotated vectors, float or __half (vec_half)
+    u32 vec_half;
     uint8_t* rec;    // [capacity * rec_bytes]
     float* e2;       // [capacity * deg] ||w-u||^2 per edge (indexing only)
     float* rot;      // [d * d]          Q (row-major)
@@ -75,7 +101,7 @@ struct pag_index {
 };
 
 struct SearchArgs {
-    const float* vec;
+    const void* vec;         // float or __half rows, see the kernel's HALF parameter
     const uint8_t* rec;
     const float* qrot;       // [nq * d] rotated queries
     const float* tables;     // [nq * Ppad * 16]
@@ -108,10 +134,13 @@ int pag_launch_rotate(hipStream_t s, const float* X, u64 rows, u32 d, const floa
 int pag_launch_tables(hipStream_t s, const float* qrot, u64 rows, const pag_layout& L, const float* cb, float* tables);
 int pag_launch_normalise(hipStream_t s, const float* X, u64 rows, u32 d, float* out);
 int pag_launch_zero_u32(hipStream_t s, u32* p, u64 count);
+int pag_launch_convert(hipStream_t s, const void* src, u32 src_half, void* dst, u32 dst_half, u64 count);   // float <-> __half, round to nearest even
 int pag_launch_exact(hipStream_t s, const pag_index* ix, const float* qrot, u64 nq, const u32* ids, u32 m, float* keys);
 int pag_launch_screen(hipStream_t s, const pag_index* ix, const float* tables, u64 nq, const u32* u, const float* Du, float* est);
 int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begin, u64 node_end);
 int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edge_list, u64 n_edges);
 
 int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid);
+inline pag_vecs pag_vecs_of(const pag_index* ix) { return pag_vecs{ ix->vec, ix->L.d, ix->vec_half }; }
+inline size_t pag_vec_elem(const pag_index* ix) { return ix->vec_half ? 2 : 4; }
 int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end);   // batch-synchronous insertion of nodes [n_begin, n_end)

@@ -107,6 +107,16 @@ __global__ void __launch_bounds__(64) k_normalise(const float* __restrict__ X, u
     for (u32 k = lane; k < d; k += 64) out[row * d + k] = (float)((double)x[k] / nrm);
 }
 
+// float -> __half (round to nearest even) or __half -> float (exact), 4 elements per thread
+__global__ void __launch_bounds__(256) k_convert(const void* __restrict__ src, u32 src_half, void* __restrict__ dst,
+                                                 u32 dst_half, u64 count) {
+    const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    const float v = src_half ? __half2float(((const __half*)src)[i]) : ((const float*)src)[i];
+    if (dst_half) ((__half*)dst)[i] = __float2half_rn(v);
+    else ((float*)dst)[i] = v;
+}
+
 __global__ void __launch_bounds__(256) k_zero_u32(u32* p, u64 count) {
     const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;
     if (i < count) p[i] = 0u;
@@ -143,6 +153,18 @@ int pag_launch_tables(hipStream_t s, const float* qrot, u64 rows, const pag_layo
 int pag_launch_normalise(hipStream_t s, const float* X, u64 rows, u32 d, float* out) {
     if (rows == 0) return PAG_OK;
     hipLaunchKernelGGL(k_normalise, dim3((unsigned)rows), dim3(64), 0, s, X, rows, d, out);
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
+}
+
+int pag_launch_convert(hipStream_t s, const void* src, u32 src_half, void* dst, u32 dst_half, u64 count) {
+    const u64 step = 1ull << 30;
+    for (u64 o = 0; o < count; o += step) {
+        const u64 c = count - o < step ? count - o : step;
+        hipLaunchKernelGGL(k_convert, dim3((unsigned)((c + 255) / 256)), dim3(256), 0, s,
+                           (const void*)((const char*)src + o * (src_half ? 2 : 4)), src_half,
+                           (void*)((char*)dst + o * (dst_half ? 2 : 4)), dst_half, c);
+    }
     PAG_HIP(hipGetLastError());
     return PAG_OK;
 }

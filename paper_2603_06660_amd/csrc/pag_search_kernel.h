@@ -137,7 +137,9 @@ __device__ __forceinline__ void rank_sort(const u64* src, u64* dst, u32 n, int l
 #define PAG_MARK(i) do {} while (0)
 #endif
 
-template <int NQ, int NW>
+// NQ: 16-byte chunks of a stored vector per lane; HALF: the store holds 16-bit floats (8 elements
+// per chunk, widened to fp32 on use) instead of fp32 (4 elements per chunk).
+template <int NQ, int NW, bool HALF>
 struct Wave {
     // constant for the kernel
     const SearchArgs A;
@@ -148,7 +150,8 @@ struct Wave {
     u64 *SA, *SB, *RF, *RT;
     u32* bitmap;
     // per query
-    float4 q[NQ];
+    static constexpr int QV = HALF ? 2 * NQ : NQ;   // float4 registers holding the query
+    float4 q[QV];
     u64 W[NW];
     u64 RL[NW];
     u32 nW, nRL;
@@ -184,19 +187,47 @@ struct Wave {
     // data has been folded into its partial sum the next vector is requested into that slot.
     static constexpr int G = NQ <= 4 ? 4 : (NQ <= 8 ? 2 : 1);
 
-    __device__ __forceinline__ void load_vec(float4 (&v)[NQ], u32 id) const {
-        const float4* p = (const float4*)(A.vec + (u64)id * A.d);
+    __device__ __forceinline__ void load_vec(uint4 (&v)[NQ], u32 id) const {
+        const uint4* p = (const uint4*)((const char*)A.vec + (u64)id * A.d * (HALF ? 2 : 4));
+        constexpr u32 per = HALF ? 8 : 4;
 #pragma unroll
         for (int c = 0; c < NQ; ++c) {
             const u32 idx = c * 64 + lane;
-            if (c < NQ - 1 || idx * 4 < A.d) v[c] = p[idx];
-            else v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c < NQ - 1 || idx * per < A.d) v[c] = p[idx];
+            else v[c] = make_uint4(0, 0, 0, 0);
         }
+    }
+
+    // sum over this lane's elements of fl32(q - x)^2, accumulated in fp64
+    __device__ __forceinline__ double lane_partial(const uint4 (&v)[NQ]) const {
+        double a = 0.0;
+#pragma unroll
+        for (int c = 0; c < NQ; ++c) {
+            if constexpr (HALF) {
+                const float2 x0 = __half22float2(*(const __half2*)&v[c].x), x1 = __half22float2(*(const __half2*)&v[c].y);
+                const float2 x2 = __half22float2(*(const __half2*)&v[c].z), x3 = __half22float2(*(const __half2*)&v[c].w);
+                const float d0 = q[2 * c].x - x0.x, d1 = q[2 * c].y - x0.y, d2 = q[2 * c].z - x1.x, d3 = q[2 * c].w - x1.y;
+                const float d4 = q[2 * c + 1].x - x2.x, d5 = q[2 * c + 1].y - x2.y;
+                const float d6 = q[2 * c + 1].z - x3.x, d7 = q[2 * c + 1].w - x3.y;
+                a = __builtin_fma((double)d0, (double)d0, a); a = __builtin_fma((double)d1, (double)d1, a);
+                a = __builtin_fma((double)d2, (double)d2, a); a = __builtin_fma((double)d3, (double)d3, a);
+                a = __builtin_fma((double)d4, (double)d4, a); a = __builtin_fma((double)d5, (double)d5, a);
+                a = __builtin_fma((double)d6, (double)d6, a); a = __builtin_fma((double)d7, (double)d7, a);
+            } else {
+                const float dx = q[c].x - __uint_as_float(v[c].x), dy = q[c].y - __uint_as_float(v[c].y);
+                const float dz = q[c].z - __uint_as_float(v[c].z), dw = q[c].w - __uint_as_float(v[c].w);
+                a = __builtin_fma((double)dx, (double)dx, a);
+                a = __builtin_fma((double)dy, (double)dy, a);
+                a = __builtin_fma((double)dz, (double)dz, a);
+                a = __builtin_fma((double)dw, (double)dw, a);
+            }
+        }
+        return a;
     }
 
     __device__ __forceinline__ float exact_keys(u32 id_lane, u64 mask) {
         float mine = 0.f;
-        float4 v[G][NQ];
+        uint4 v[G][NQ];
         u64 m_issue = mask, m_done = mask;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -216,16 +247,7 @@ struct Wave {
                 if (m_done) {
                     pl[g] = __ffsll((long long)m_done) - 1;
                     m_done &= m_done - 1;
-                    double a = 0.0;
-#pragma unroll
-                    for (int c = 0; c < NQ; ++c) {
-                        const float dx = q[c].x - v[g][c].x, dy = q[c].y - v[g][c].y;
-                        const float dz = q[c].z - v[g][c].z, dw = q[c].w - v[g][c].w;
-                        a = __builtin_fma((double)dx, (double)dx, a);
-                        a = __builtin_fma((double)dy, (double)dy, a);
-                        a = __builtin_fma((double)dz, (double)dz, a);
-                        a = __builtin_fma((double)dw, (double)dw, a);
-                    }
+                    const double a = lane_partial(v[g]);
                     acc[g] = a;
                     if (m_issue) {
                         const int p = __ffsll((long long)m_issue) - 1;
@@ -337,7 +359,13 @@ struct Wave {
 #pragma unroll
             for (int c = 0; c < NQ; ++c) {
                 const u32 idx = c * 64 + lane;
-                q[c] = (c < NQ - 1 || idx * 4 < d) ? qp[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+                if constexpr (HALF) {
+                    const bool in = c < NQ - 1 || idx * 8 < d;
+                    q[2 * c] = in ? qp[2 * idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    q[2 * c + 1] = in ? qp[2 * idx + 1] : make_float4(0.f, 0.f, 0.f, 0.f);
+                } else {
+                    q[c] = (c < NQ - 1 || idx * 4 < d) ? qp[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
             }
             const float4* tp = (const float4*)(A.tables + (u64)qi * A.Ppad * PAG_NCODE);
             for (u32 i = lane; i < A.Ppad * PAG_NCODE / 4; i += 64) ((float4*)T)[i] = tp[i];
@@ -573,14 +601,14 @@ struct Wave {
 // Persistent waves: every wave pulls query numbers from one counter until the batch is drained,
 // so long and short searches balance themselves; the loop ends for every wave once the counter
 // passes nq.
-template <int NQ, int NW>
+template <int NQ, int NW, bool HALF>
 #ifdef PAG_WAVES_PER_EU
 __attribute__((amdgpu_waves_per_eu(PAG_WAVES_PER_EU, 8)))
 #endif
 __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x;
-    Wave<NQ, NW> w(A, smem, lane);
+    Wave<NQ, NW, HALF> w(A, smem, lane);
     for (;;) {
         u32 qi = 0;
         if (lane == 0) qi = atomicAdd(A.qcounter, 1u);
@@ -593,6 +621,3 @@ __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
 
 }  // namespace pagk
 
-#define PAG_INSTANTIATE_SEARCH(NQ)                                                          \
-    template __global__ void pagk::k_search<NQ, 1>(const SearchArgs);                      \
-    template __global__ void pagk::k_search<NQ, 2>(const SearchArgs);

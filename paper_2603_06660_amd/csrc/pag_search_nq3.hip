@@ -1,7 +1,9 @@
-// Instantiation of the search kernel for vectors of up to 768 floats (3 float4 per lane).
+// Instantiations of the search kernel for stored vectors of up to 3 16-byte chunks per lane
+// (fp32 rows of up to 768 elements; 16-bit rows of up to 1536 elements).
 #include "pag_search_kernel.h"
 
 typedef void (*pag_search_fn)(const SearchArgs);
-pag_search_fn pag_search_fn_nq3(int nw) {
-    return nw == 1 ? (pag_search_fn)pagk::k_search<3, 1> : (pag_search_fn)pagk::k_search<3, 2>;
+pag_search_fn pag_search_fn_nq3(int nw, bool half) {
+    if (half) return nw == 1 ? (pag_search_fn)pagk::k_search<3, 1, true> : (pag_search_fn)pagk::k_search<3, 2, true>;
+    return nw == 1 ? (pag_search_fn)pagk::k_search<3, 1, false> : (pag_search_fn)pagk::k_search<3, 2, false>;
 }

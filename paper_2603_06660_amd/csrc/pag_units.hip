@@ -11,7 +11,7 @@ __device__ __forceinline__ double wave_sum(double x) {
 }
 
 // keys[i*m+j] = fl32( sum_k fl32(q_i[k] - x_id[k])^2 ), one wave per (i, j); float4 loads.
-__global__ void __launch_bounds__(64) k_exact(const float* __restrict__ vec, const float* __restrict__ qrot,
+__global__ void __launch_bounds__(64) k_exact(pag_vecs V, const float* __restrict__ qrot,
                                               u64 nq, u32 d, u64 n, const u32* __restrict__ ids, u32 m,
                                               float* __restrict__ keys) {
     const u64 pair = blockIdx.x;
@@ -20,10 +20,9 @@ __global__ void __launch_bounds__(64) k_exact(const float* __restrict__ vec, con
     const u32 id = ids[pair];
     if (id >= n) { if (lane == 0) keys[pair] = __builtin_nanf(""); return; }
     const float4* q = (const float4*)(qrot + (pair / m) * d);
-    const float4* x = (const float4*)(vec + (u64)id * d);
     double acc = 0.0;
     for (u32 c = lane; c < d / 4; c += 64) {
-        const float4 a = q[c], b = x[c];
+        const float4 a = q[c], b = pag_vload4(V, id, c);
         const float dx = a.x - b.x, dy = a.y - b.y, dz = a.z - b.z, dw = a.w - b.w;
         acc = __builtin_fma((double)dx, (double)dx, acc);
         acc = __builtin_fma((double)dy, (double)dy, acc);
@@ -73,7 +72,7 @@ __global__ void __launch_bounds__(64) k_screen(const uint8_t* __restrict__ recs,
 //   e2 = ||w-u||^2, maxsum = sum_l best_l, off = sum_l <u_l, r*_l>  (l ascending)
 //   a = ||w-u|| / max(maxsum/||w-u||, 1e-6), c = e2 + 2 a off; both 0 when w == u
 // Lane l owns subspace l (l, l+64, ...).  Results go straight into the adjacency record and e2.
-__global__ void __launch_bounds__(64) k_edge_info(const float* __restrict__ vec, uint8_t* __restrict__ recs,
+__global__ void __launch_bounds__(64) k_edge_info(pag_vecs V, uint8_t* __restrict__ recs,
                                                   float* __restrict__ e2_out, pag_layout L,
                                                   const float* __restrict__ cb, const u32* __restrict__ edges,
                                                   u64 n_edges, u64 node_begin) {
@@ -105,11 +104,9 @@ __global__ void __launch_bounds__(64) k_edge_info(const float* __restrict__ vec,
         if ((u32)lane < L.cw) cw_out[lane] = 0u;
         return;
     }
-    const float* up = vec + (u64)u * L.d;
-    const float* wp = vec + (u64)w * L.d;
     double e2p = 0.0;
     for (u32 k = lane; k < L.d; k += 64) {
-        const float a = up[k], df = wp[k] - a;
+        const float a = pag_vload1(V, u, k), df = pag_vload1(V, w, k) - a;
         uu[k] = a; diff[k] = df;
         e2p = __builtin_fma((double)df, (double)df, e2p);
     }
@@ -162,7 +159,7 @@ int pag_launch_exact(hipStream_t s, const pag_index* ix, const float* qrot, u64 
     const u64 pairs = nq * m;
     if (pairs == 0) return PAG_OK;
     if (pairs > 0x7FFFFFFFull) { pag_set_error("pag_exact_distances: more than 2^31-1 pairs"); return PAG_EINVAL; }
-    hipLaunchKernelGGL(k_exact, dim3((unsigned)pairs), dim3(64), 0, s, ix->vec, qrot, nq, ix->L.d, ix->n, ids, m, keys);
+    hipLaunchKernelGGL(k_exact, dim3((unsigned)pairs), dim3(64), 0, s, pag_vecs_of(ix), qrot, nq, ix->L.d, ix->n, ids, m, keys);
     PAG_HIP(hipGetLastError());
     return PAG_OK;
 }
@@ -187,7 +184,7 @@ int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begi
         const u64 ne = nb + nodes_per < node_end ? nb + nodes_per : node_end;
         if (nb >= node_end) break;
         hipLaunchKernelGGL(k_edge_info, dim3((unsigned)((ne - nb) * ix->L.deg)), dim3(64), edge_info_lds(ix->L), s,
-                           ix->vec, ix->rec, ix->e2, ix->L, ix->cb, (const u32*)nullptr, 0ull, nb);
+                           pag_vecs_of(ix), ix->rec, ix->e2, ix->L, ix->cb, (const u32*)nullptr, 0ull, nb);
     }
     PAG_HIP(hipGetLastError());
     return PAG_OK;
@@ -195,7 +192,7 @@ int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begi
 
 int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edge_list, u64 n_edges) {
     if (n_edges == 0) return PAG_OK;
-    hipLaunchKernelGGL(k_edge_info, dim3((unsigned)n_edges), dim3(64), edge_info_lds(ix->L), s, ix->vec, ix->rec,
+    hipLaunchKernelGGL(k_edge_info, dim3((unsigned)n_edges), dim3(64), edge_info_lds(ix->L), s, pag_vecs_of(ix), ix->rec,
                        ix->e2, ix->L, ix->cb, edge_list, n_edges, 0ull);
     PAG_HIP(hipGetLastError());
     return PAG_OK;

@@ -168,3 +168,45 @@ def test_pes_switch(orc, cfg1_small, built):
     r0 = wl.recall_at_k(gix0.search(qd, w.K, 64)[0].cpu().numpy(), gt)
     r1 = wl.recall_at_k(built[0].search(qd, w.K, 64)[0].cpu().numpy(), gt)
     assert r1 >= r0 - 0.01 and r0 >= 0.94
+
+
+def test_fp16_vector_store(orc, cfg1_small, cfg1_oracle_index):
+    """16-bit vector payload (Sec. 4.2): the index holds fl16(fl32(Q x)); all arithmetic on those values is
+    unchanged, so the oracle -- given the rounded vectors as fp32 -- must agree exactly as before."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_FP16_VECTORS
+    w, base, q, gt, gtk = cfg1_small
+    # (1) oracle-built index over rounded vectors, imported into a 16-bit store
+    oix = orc.OracleIndex.build(base, w.metric, deg=w.deg, P=w.P, efC=100, seed=11, vec_f16=True)
+    gix = PagIndex.from_arrays(oix.vec, oix.adj, oix.a, oix.c, oix.e2, oix.codes, oix.rot, oix.cb, oix.entry,
+                               metric="l2", flags=FLAG_FP16_VECTORS)
+    qd = torch.from_numpy(q).cuda()
+    for efS in (32, 128):
+        gi, gd = gix.search(qd, w.K, efS)
+        oi, od, _ = oix.search(q, w.K, efS)
+        assert (gi.cpu().numpy() == oi).mean() >= 0.999
+        assert np.allclose(gd.cpu().numpy(), od, rtol=1e-5)
+    codes, a, c, e2 = gix.edge_info(0, 300)
+    assert np.array_equal(codes, oix.codes[:300]) and np.allclose(a, oix.a[:300], rtol=2e-7, atol=0)
+    # (2) GPU-built index with a 16-bit store
+    gix2 = PagIndex.build(torch.from_numpy(base).cuda(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                          ef_construction=100, seed=21, flags=FLAG_FP16_VECTORS)
+    ex = gix2.export()
+    assert np.array_equal(ex["vectors"], ex["vectors"].astype(np.float16).astype(np.float32))
+    ref = np.stack([orc.rotate(ex["rotation"], x) for x in base[:300]]).astype(np.float16).astype(np.float32)
+    assert (ref == ex["vectors"][:300]).mean() >= 0.9999
+    oix2 = _oracle_view(orc, ex)
+    codes, a, c, e2 = oix2.recompute_edge_info(0, base.shape[0])
+    assert np.array_equal(codes, ex["codes"]) and np.allclose(a, ex["a"], rtol=2e-7, atol=0)
+    gi, gd = gix2.search(qd, w.K, 64)
+    oi, od, _ = oix2.search(q, w.K, 64)
+    assert (gi.cpu().numpy() == oi).mean() >= 0.999
+    # recall against the fp32 ground truth is that of an fp32 index within noise
+    r16 = wl.recall_at_k(gi.cpu().numpy(), gt)
+    assert r16 >= 0.95
+    # online insertion into a 16-bit store
+    gix3 = PagIndex.build(torch.from_numpy(base[:2000]).cuda(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                          ef_construction=100, seed=21, flags=FLAG_FP16_VECTORS, capacity=3000)
+    gix3.insert(torch.from_numpy(base[2000:]).cuda())
+    gi3, _ = gix3.search(qd, w.K, 64)
+    assert wl.recall_at_k(gi3.cpu().numpy(), gt) >= 0.95
