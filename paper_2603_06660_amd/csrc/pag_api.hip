@@ -129,12 +129,12 @@ int make_layout(uint32_t d, uint32_t P, uint32_t deg, pag_layout* L) {
     PAG_CHECK(P <= 8 * PAG_MAX_CW, PAG_EUNSUPPORTED, "this build needs num_subspaces <= 64");
     PAG_CHECK(deg <= PAG_MAX_DEG, PAG_EUNSUPPORTED, "this build needs max_degree <= 64");
     L->d = d; L->P = P; L->dsub = d / P; L->deg = deg;
-    L->Ppad = (P + 15) / 16 * 16;
+    L->Ppad = P <= 16 ? 16 : (P <= 32 ? 32 : 64);
     L->cw = L->Ppad / 8;
     L->off_a = deg * 4;
     L->off_c = deg * 8;
-    L->off_codes = deg * 12;
-    L->rec_bytes = (deg * 12 + deg * L->cw * 4 + 127) / 128 * 128;
+    L->off_codes = (deg * 12 + 15) / 16 * 16;
+    L->rec_bytes = (L->off_codes + deg * L->cw * 4 + 127) / 128 * 128;
     return PAG_OK;
 }
 

@@ -37,11 +37,11 @@ enum {
 };
 
 // Adjacency record of node u (one burst of whole 128-byte lines):
-//   [ids deg x u32][a deg x f32][c deg x f32][codes deg x (cw dwords)]   padded to 128 bytes
+//   [ids deg x u32][a deg x f32][c deg x f32][pad to 16 B][codes deg x (cw dwords)]   padded to 128 bytes
 // codes of neighbour slot s: dword l/8 of its chunk holds the code of subspace l in bits 4*(l%8).
 struct pag_layout {
     u32 d, P, dsub, deg;
-    u32 Ppad;        // P rounded up to a multiple of 16 (table rows beyond P are zero)
+    u32 Ppad;        // P rounded up to 16, 32 or 64 (table rows beyond P are zero)
     u32 cw;          // code dwords per neighbour = Ppad / 8
     u32 rec_bytes;   // record size
     u32 off_a, off_c, off_codes;

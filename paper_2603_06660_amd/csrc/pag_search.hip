@@ -3,25 +3,47 @@
 #include "pag_internal.h"
 
 typedef void (*pag_search_fn)(const SearchArgs);
-pag_search_fn pag_search_fn_nq1(int, bool);
-pag_search_fn pag_search_fn_nq2(int, bool);
-pag_search_fn pag_search_fn_nq3(int, bool);
-pag_search_fn pag_search_fn_nq4(int, bool);
-pag_search_fn pag_search_fn_nq6(int, bool);
-pag_search_fn pag_search_fn_nq8(int, bool);
-pag_search_fn pag_search_fn_nq12(int, bool);
+pag_search_fn pag_search_fn_nq1_cw2(int, bool);
+pag_search_fn pag_search_fn_nq1_cw4(int, bool);
+pag_search_fn pag_search_fn_nq1_cw8(int, bool);
+pag_search_fn pag_search_fn_nq2_cw2(int, bool);
+pag_search_fn pag_search_fn_nq2_cw4(int, bool);
+pag_search_fn pag_search_fn_nq2_cw8(int, bool);
+pag_search_fn pag_search_fn_nq3_cw2(int, bool);
+pag_search_fn pag_search_fn_nq3_cw4(int, bool);
+pag_search_fn pag_search_fn_nq3_cw8(int, bool);
+pag_search_fn pag_search_fn_nq4_cw2(int, bool);
+pag_search_fn pag_search_fn_nq4_cw4(int, bool);
+pag_search_fn pag_search_fn_nq4_cw8(int, bool);
+pag_search_fn pag_search_fn_nq6_cw2(int, bool);
+pag_search_fn pag_search_fn_nq6_cw4(int, bool);
+pag_search_fn pag_search_fn_nq6_cw8(int, bool);
+pag_search_fn pag_search_fn_nq8_cw2(int, bool);
+pag_search_fn pag_search_fn_nq8_cw4(int, bool);
+pag_search_fn pag_search_fn_nq8_cw8(int, bool);
+pag_search_fn pag_search_fn_nq12_cw2(int, bool);
+pag_search_fn pag_search_fn_nq12_cw4(int, bool);
+pag_search_fn pag_search_fn_nq12_cw8(int, bool);
 
-static pag_search_fn pick(u32 d, u32 b, bool half) {
+static pag_search_fn pick(u32 d, u32 b, bool half, u32 cw) {
     const int nw = b <= 64 ? 1 : 2;
     const u32 per_chunk_row = half ? 512 : 256;       // elements covered by one 16-byte chunk per lane
     const u32 chunks = (d + per_chunk_row - 1) / per_chunk_row;
-    if (chunks <= 1) return pag_search_fn_nq1(nw, half);
-    if (chunks <= 2) return pag_search_fn_nq2(nw, half);
-    if (chunks <= 3) return pag_search_fn_nq3(nw, half);
-    if (chunks <= 4) return pag_search_fn_nq4(nw, half);
-    if (chunks <= 6) return pag_search_fn_nq6(nw, half);
-    if (chunks <= 8) return pag_search_fn_nq8(nw, half);
-    if (chunks <= 12) return pag_search_fn_nq12(nw, half);
+#define PAG_PICK_CW(NQ)                                              \
+    switch (cw) {                                                    \
+        case 2: return pag_search_fn_nq##NQ##_cw2(nw, half);         \
+        case 4: return pag_search_fn_nq##NQ##_cw4(nw, half);         \
+        case 8: return pag_search_fn_nq##NQ##_cw8(nw, half);         \
+        default: return nullptr;                                     \
+    }
+    if (chunks <= 1) { PAG_PICK_CW(1) }
+    if (chunks <= 2) { PAG_PICK_CW(2) }
+    if (chunks <= 3) { PAG_PICK_CW(3) }
+    if (chunks <= 4) { PAG_PICK_CW(4) }
+    if (chunks <= 6) { PAG_PICK_CW(6) }
+    if (chunks <= 8) { PAG_PICK_CW(8) }
+    if (chunks <= 12) { PAG_PICK_CW(12) }
+#undef PAG_PICK_CW
     return nullptr;
 }
 
@@ -43,7 +65,7 @@ int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, u32 blog, SearchA
 }
 
 int pag_search_max_grid(const pag_index* ix, u32 b, u32 lds_bytes, int* grid) {
-    pag_search_fn fn = pick(ix->L.d, b, ix->vec_half != 0);
+    pag_search_fn fn = pick(ix->L.d, b, ix->vec_half != 0, ix->L.cw);
     if (!fn) { pag_set_error("search: dimension above 3072 is not built"); return PAG_EUNSUPPORTED; }
     int per_cu = 0;
     PAG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)fn, 64, lds_bytes));
@@ -53,7 +75,7 @@ int pag_search_max_grid(const pag_index* ix, u32 b, u32 lds_bytes, int* grid) {
 }
 
 int pag_launch_search(const pag_index* ix, const SearchArgs& a, u32 lds_bytes, int* grid_io) {
-    pag_search_fn fn = pick(a.d, a.b, ix->vec_half != 0);
+    pag_search_fn fn = pick(a.d, a.b, ix->vec_half != 0, a.cw);
     if (!fn) { pag_set_error("search: dimension above 3072 is not built"); return PAG_EUNSUPPORTED; }
     int grid = *grid_io;
     if ((u64)grid > a.nq) grid = (int)a.nq;

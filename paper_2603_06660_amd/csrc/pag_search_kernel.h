@@ -28,6 +28,12 @@ __device__ __forceinline__ u64 rdlane64(u64 v, int l) {
     u32 lo = rdlane((u32)v, l), hi = rdlane((u32)(v >> 32), l);
     return ((u64)hi << 32) | lo;
 }
+// The workgroup is a single wavefront and its LDS operations execute in program order, so all that
+// cross-lane LDS traffic needs is that the compiler keeps the accesses in place and that the LDS
+// queue has drained.  Unlike __syncthreads() this does not wait for global loads in flight
+// (prefetched records, seen-set words), which is the point.
+__device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ u32 uniform(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
 
 template <int CTRL>
@@ -137,9 +143,29 @@ __device__ __forceinline__ void rank_sort(const u64* src, u64* dst, u32 n, int l
 #define PAG_MARK(i) do {} while (0)
 #endif
 
-// NQ: 16-byte chunks of a stored vector per lane; HALF: the store holds 16-bit floats (8 elements
-// per chunk, widened to fp32 on use) instead of fp32 (4 elements per chunk).
-template <int NQ, int NW, bool HALF>
+// S = sum_l T[l][code_l] over the CW * 8 subspaces of one neighbour, added in increasing l.
+// The LDS gathers of 16 subspaces are issued together, then consumed in order.
+template <int CW>
+__device__ __forceinline__ float table_sum(const float* T, const u32 (&cwv)[CW]) {
+    float S = 0.f;
+#pragma unroll
+    for (int k = 0; k < CW; k += 2) {
+        float t[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const u32 wd = cwv[k + j / 8];
+            t[j] = T[(k * 8 + j) * PAG_NCODE + ((wd >> (4 * (j % 8))) & 15u)];
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) S = S + t[j];
+    }
+    return S;
+}
+
+// NQ: 16-byte chunks of a stored vector per lane; NW: entries of W / R_L per lane; HALF: the store
+// holds 16-bit floats (8 elements per chunk, widened to fp32 on use) instead of fp32 (4 per chunk);
+// CW: dwords of 4-bit codes per neighbour (2, 4 or 8 for up to 16, 32 or 64 subspaces).
+template <int NQ, int NW, bool HALF, int CW>
 struct Wave {
     // constant for the kernel
     const SearchArgs A;
@@ -157,6 +183,12 @@ struct Wave {
     u32 nW, nRL;
     u32 cntF, hdF, cntT, hdT;       // rings: valid entries (<= b) and total pushes; slot = push number & ring mask
     u32 n_hash, n_spill;
+    u32 tail_idx;                   // chunk index this lane reads for the last 16-byte chunk of a row (0 if past the end)
+    bool tail_ok;
+    // adjacency record requested ahead of time for the node that will be expanded next
+    u32 nx_id;                      // whose record pf_* holds (PAG_EMPTY: none)
+    u32 pf_id, pf_cw[CW];
+    float pf_a, pf_c;
     u64 Hk;                         // indexing: PES buffer H(v), lane i = i-th closest surviving node (Alg. 1)
     // statistics (wave-uniform)
     u32 s_hops, s_tests, s_passes, s_exact, s_rounds, s_rf, s_rt, s_spill, s_queries;
@@ -174,11 +206,64 @@ struct Wave {
         RF = (u64*)(smem + a.off_rf);
         RT = (u64*)(smem + a.off_rt);
         bitmap = a.bitmap + (u64)blockIdx.x * a.bitmap_words;
+        tail_ok = ((NQ - 1) * 64 + (u32)ln) * (HALF ? 8u : 4u) < a.d;
+        tail_idx = tail_ok ? (NQ - 1) * 64 + (u32)ln : 0u;
         s_hops = s_tests = s_passes = s_exact = s_rounds = s_rf = s_rt = s_spill = s_queries = 0;
 #ifdef PAG_PHASE_TIMERS
         for (int i = 0; i < 6; ++i) s_phase[i] = 0;
         t_last = wall_clock64();
 #endif
+    }
+
+    // lane s < deg reads neighbour slot s of node u: id, a, c and its chunk of 4-bit codes
+    __device__ __forceinline__ void load_record(u32 u, u32& id, float& ea, float& ec, u32 (&cwv)[CW]) const {
+        const uint8_t* rec = A.rec + (u64)u * A.rec_bytes;
+        id = PAG_EMPTY; ea = 0.f; ec = 0.f;
+#pragma unroll
+        for (int k = 0; k < CW; ++k) cwv[k] = 0;
+        if ((u32)lane < A.deg) {
+            id = ((const u32*)rec)[lane];
+            ea = ((const float*)(rec + A.off_a))[lane];
+            ec = ((const float*)(rec + A.off_c))[lane];
+            const u32* cp = (const u32*)(rec + A.off_codes) + (u32)lane * CW;   // 16-byte aligned section
+            if constexpr (CW == 2) {
+                const uint2 t = *(const uint2*)cp;
+                cwv[0] = t.x; cwv[1] = t.y;
+            } else {
+#pragma unroll
+                for (int k = 0; k < CW; k += 4) {
+                    const uint4 t = *(const uint4*)(cp + k);
+                    cwv[k] = t.x; cwv[k + 1] = t.y; cwv[k + 2] = t.z; cwv[k + 3] = t.w;
+                }
+            }
+        }
+    }
+
+    // The node expanded next is the unvisited entry with the smallest rank after the merge: either the
+    // first unvisited member of W or the smallest passer.  Both are known before W is physically
+    // rebuilt, so its adjacency record is requested here and arrives while the merge completes.
+    __device__ __forceinline__ void request_next(const u32 (&cntW)[NW], bool pass, u32 cP, u32 rP, u32 id_lane) {
+        const u32 b = A.b;
+        u32 best_r = 0xFFFFFFFFu, best_id = PAG_EMPTY;
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
+            const u32 idx = s * 64 + lane;
+            const u32 r = idx + cntW[s];
+            const u64 m = __ballot(idx < nW && !(W[s] & 1ull) && r < b);
+            if (m && best_r == 0xFFFFFFFFu) {
+                const int l = __ffsll((long long)m) - 1;
+                best_r = rdlane(r, l);
+                best_id = rdlane((u32)(W[s] & 0xFFFFFFFFull), l) >> 1;
+            }
+        }
+        const u64 m2 = __ballot(pass && cP == 0 && rP < b);
+        if (m2) {
+            const int l = __ffsll((long long)m2) - 1;
+            const u32 r2 = rdlane(rP, l);
+            if (r2 < best_r) { best_r = r2; best_id = rdlane(id_lane, l); }
+        }
+        nx_id = best_id;
+        if (best_id != PAG_EMPTY) load_record(best_id, pf_id, pf_a, pf_c, pf_cw);
     }
 
     // exact keys ||q - x_id||^2 (Alg. 2, "compute the distance") for the lanes in `mask`;
@@ -187,15 +272,15 @@ struct Wave {
     // data has been folded into its partial sum the next vector is requested into that slot.
     static constexpr int G = NQ <= 4 ? 4 : (NQ <= 8 ? 2 : 1);
 
+    // Branch-free row load: only the last chunk can run past the row; there the lane re-reads chunk
+    // 0 (in bounds) and the value is replaced by zeros, so no load ever sits inside a branch and the
+    // loads of several rows stay in flight together.
     __device__ __forceinline__ void load_vec(uint4 (&v)[NQ], u32 id) const {
         const uint4* p = (const uint4*)((const char*)A.vec + (u64)id * A.d * (HALF ? 2 : 4));
-        constexpr u32 per = HALF ? 8 : 4;
 #pragma unroll
-        for (int c = 0; c < NQ; ++c) {
-            const u32 idx = c * 64 + lane;
-            if (c < NQ - 1 || idx * per < A.d) v[c] = p[idx];
-            else v[c] = make_uint4(0, 0, 0, 0);
-        }
+        for (int c = 0; c < NQ - 1; ++c) v[c] = p[c * 64 + lane];
+        const uint4 t = p[tail_idx];
+        v[NQ - 1] = tail_ok ? t : make_uint4(0, 0, 0, 0);
     }
 
     // sum over this lane's elements of fl32(q - x)^2, accumulated in fp64
@@ -272,7 +357,13 @@ struct Wave {
     // Admission of the lanes in `mask` (ids in id_lane): exact keys, seen-set insertion, merge into W.
     __device__ __forceinline__ void admit(u32 id_lane, u64 mask) {
         const u32 np = (u32)__popcll(mask);
-        if (np == 0) return;
+        if (np == 0) {
+            u32 zero[NW];
+#pragma unroll
+            for (int s = 0; s < NW; ++s) zero[s] = 0;
+            request_next(zero, false, 0, 0, id_lane);
+            return;
+        }
         const u32 b = A.b;
         const bool pass = (mask >> lane) & 1ull;
         PAG_MARK(2);
@@ -314,6 +405,7 @@ struct Wave {
         const u32 n_ins = (u32)__popcll(__ballot(pass && rP < b)); // passers that enter W
         const u32 n_f = np - n_ins;                                // false positives -> R_F
         const u32 n_ej = nW + n_ins - nW2;                         // displaced members -> R_T
+        request_next(cntW, pass, cP, rP, id_lane);
 #pragma unroll
         for (int s = 0; s < NW; ++s) {
             const u32 idx = s * 64 + lane;
@@ -340,14 +432,14 @@ struct Wave {
             cntF = cntF + n_f < b ? cntF + n_f : b;
             hdF += n_f;
         }
-        __syncthreads();
+        lds_sync();
 #pragma unroll
         for (int s = 0; s < NW; ++s) {
             const u32 idx = s * 64 + lane;
             W[s] = idx < nW2 ? SA[idx] : PAG_KEY_INVALID;
         }
         nW = nW2;
-        __syncthreads();
+        lds_sync();
         PAG_MARK(4);
     }
 
@@ -381,6 +473,7 @@ struct Wave {
             cntF = hdF = cntT = hdT = 0;
             n_hash = n_spill = 0;
             Hk = PAG_KEY_INVALID;
+            nx_id = PAG_EMPTY;
             __syncthreads();
         }
         s_queries++;
@@ -432,26 +525,18 @@ struct Wave {
                         if ((int)(wr >> 6) == s) Dmax = __uint_as_float(rdlane((u32)(W[s] >> 32), wr & 63));
                 }
                 PAG_MARK(0);
-                // adjacency record of u
-                const uint8_t* rec = A.rec + (u64)u * A.rec_bytes;
-                u32 id = PAG_EMPTY;
-                float ea = 0.f, ec = 0.f;
-                u32 cwv[PAG_MAX_CW];
+                // adjacency record of u: normally already on its way (see request_next)
+                u32 id;
+                float ea, ec;
+                u32 cwv[CW];
+                if (u == nx_id) {
+                    id = pf_id; ea = pf_a; ec = pf_c;
 #pragma unroll
-                for (int k = 0; k < PAG_MAX_CW; ++k) cwv[k] = 0;
-                if ((u32)lane < deg) {
-                    id = ((const u32*)rec)[lane];
-                    ea = ((const float*)(rec + A.off_a))[lane];
-                    ec = ((const float*)(rec + A.off_c))[lane];
-                    const u32* cp = (const u32*)(rec + A.off_codes) + (u32)lane * A.cw;
-#pragma unroll
-                    for (int k = 0; k < PAG_MAX_CW; k += 2) {
-                        if ((u32)k < A.cw) {
-                            const uint2 t = *(const uint2*)(cp + k);
-                            cwv[k] = t.x; cwv[k + 1] = t.y;
-                        }
-                    }
+                    for (int k = 0; k < CW; ++k) cwv[k] = pf_cw[k];
+                } else {
+                    load_record(u, id, ea, ec, cwv);
                 }
+                nx_id = PAG_EMPTY;
                 PAG_MARK(1);
                 const bool in_graph = id != PAG_EMPTY && id < A.n_limit;
                 // seen-set lookup: LDS hash, then (for ids that may live in the HBM bitmap according to
@@ -468,15 +553,7 @@ struct Wave {
                 if (!(A.flags & PAG_FLAG_NO_PRT)) {
                     float S = 0.f;
                     if (cand || (want_pes && in_graph)) {
-#pragma unroll
-                        for (int k = 0; k < PAG_MAX_CW; ++k) {
-                            if ((u32)k < A.cw) {
-                                const u32 wd = cwv[k];
-#pragma unroll
-                                for (int t = 0; t < 8; ++t)
-                                    S = S + T[(k * 8 + t) * PAG_NCODE + ((wd >> (4 * t)) & 15u)];
-                            }
-                        }
+                        S = table_sum<CW>(T, cwv);
                     }
                     est = __builtin_fmaf(-2.0f * ea, S, Du + ec);
                 }
@@ -503,6 +580,7 @@ struct Wave {
             }
 
             // ---- round end (Alg. 2): W -> R_L, clear W; merge + sort rings; refill W; rest -> R_T ----
+            nx_id = PAG_EMPTY;
             if (A.cand) {
                 // indexing: R_L has room for every round's W (capacity efC >= Rmax * b is enforced by the host)
 #pragma unroll
@@ -518,25 +596,25 @@ struct Wave {
                     if (idx < nRL) SA[idx] = RL[s];
                     if (idx < nW) SA[nRL + idx] = W[s];
                 }
-                __syncthreads();
+                lds_sync();
                 const u32 n = nRL + nW;
                 rank_sort(SA, SB, n, lane);
-                __syncthreads();
+                lds_sync();
                 nRL = n < A.K ? n : A.K;
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
                     const u32 idx = s * 64 + lane;
                     RL[s] = idx < nRL ? SB[idx] : PAG_KEY_INVALID;
                 }
-                __syncthreads();
+                lds_sync();
             }
             {
                 for (u32 i = lane; i < cntF; i += 64) SA[i] = RF[(hdF - cntF + i) & A.ring_mask];
                 for (u32 i = lane; i < cntT; i += 64) SA[cntF + i] = RT[(hdT - cntT + i) & A.ring_mask];
-                __syncthreads();
+                lds_sync();
                 const u32 n = cntF + cntT;
                 rank_sort(SA, SB, n, lane);
-                __syncthreads();
+                lds_sync();
                 nW = n < b ? n : b;
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
@@ -547,7 +625,7 @@ struct Wave {
                 for (u32 j = lane; j < rest; j += 64) RT[j] = SB[n - 1 - j];
                 cntT = rest; hdT = rest;
                 cntF = 0; hdF = 0;
-                __syncthreads();
+                lds_sync();
             }
         }
 
@@ -601,14 +679,14 @@ struct Wave {
 // Persistent waves: every wave pulls query numbers from one counter until the batch is drained,
 // so long and short searches balance themselves; the loop ends for every wave once the counter
 // passes nq.
-template <int NQ, int NW, bool HALF>
+template <int NQ, int NW, bool HALF, int CW>
 #ifdef PAG_WAVES_PER_EU
 __attribute__((amdgpu_waves_per_eu(PAG_WAVES_PER_EU, 8)))
 #endif
 __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x;
-    Wave<NQ, NW, HALF> w(A, smem, lane);
+    Wave<NQ, NW, HALF, CW> w(A, smem, lane);
     for (;;) {
         u32 qi = 0;
         if (lane == 0) qi = atomicAdd(A.qcounter, 1u);
