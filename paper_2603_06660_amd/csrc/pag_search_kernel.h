@@ -184,7 +184,7 @@ struct Wave {
     u32 cntF, hdF, cntT, hdT;       // rings: valid entries (<= b) and total pushes; slot = push number & ring mask
     u32 n_hash, n_spill;
     u32 tail_idx;                   // chunk index this lane reads for the last 16-byte chunk of a row (0 if past the end)
-    bool tail_ok;
+    u32 tail_mask;                  // all ones if that chunk lies inside the row, else zero
     // adjacency record requested ahead of time for the node that will be expanded next
     u32 nx_id;                      // whose record pf_* holds (PAG_EMPTY: none)
     u32 pf_id, pf_cw[CW];
@@ -206,8 +206,9 @@ struct Wave {
         RF = (u64*)(smem + a.off_rf);
         RT = (u64*)(smem + a.off_rt);
         bitmap = a.bitmap + (u64)blockIdx.x * a.bitmap_words;
-        tail_ok = ((NQ - 1) * 64 + (u32)ln) * (HALF ? 8u : 4u) < a.d;
+        const bool tail_ok = ((NQ - 1) * 64 + (u32)ln) * (HALF ? 8u : 4u) < a.d;
         tail_idx = tail_ok ? (NQ - 1) * 64 + (u32)ln : 0u;
+        tail_mask = tail_ok ? 0xFFFFFFFFu : 0u;
         s_hops = s_tests = s_passes = s_exact = s_rounds = s_rf = s_rt = s_spill = s_queries = 0;
 #ifdef PAG_PHASE_TIMERS
         for (int i = 0; i < 6; ++i) s_phase[i] = 0;
@@ -268,9 +269,10 @@ struct Wave {
 
     // exact keys ||q - x_id||^2 (Alg. 2, "compute the distance") for the lanes in `mask`;
     // lane p receives the key of its own id.  Differences in fp32, squares summed in fp64,
-    // one rounding to fp32 at the end.  G vectors are in flight at a time: as soon as a slot's
-    // data has been folded into its partial sum the next vector is requested into that slot.
-    static constexpr int G = NQ <= 4 ? 4 : (NQ <= 8 ? 2 : 1);
+    // one rounding to fp32 at the end.  Two buffers of GB vectors each alternate: while one is
+    // reduced the other one's loads are in flight.  No load sits inside a branch (a buffer without
+    // a passer left simply re-reads the last row), which keeps the wait counts exact.
+    static constexpr int GB = NQ <= 4 ? 2 : 1;
 
     // Branch-free row load: only the last chunk can run past the row; there the lane re-reads chunk
     // 0 (in bounds) and the value is replaced by zeros, so no load ever sits inside a branch and the
@@ -280,7 +282,7 @@ struct Wave {
 #pragma unroll
         for (int c = 0; c < NQ - 1; ++c) v[c] = p[c * 64 + lane];
         const uint4 t = p[tail_idx];
-        v[NQ - 1] = tail_ok ? t : make_uint4(0, 0, 0, 0);
+        v[NQ - 1] = make_uint4(t.x & tail_mask, t.y & tail_mask, t.z & tail_mask, t.w & tail_mask);
     }
 
     // sum over this lane's elements of fl32(q - x)^2, accumulated in fp64
@@ -310,46 +312,49 @@ struct Wave {
         return a;
     }
 
+    // request the rows of the next GB passers (or, when none is left, the last row again)
+    __device__ __forceinline__ void issue(uint4 (&buf)[GB][NQ], int (&pl)[GB], u64& m, int& last, u32 id_lane) const {
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+            pl[g] = -1;
+            if (m) { last = __ffsll((long long)m) - 1; m &= m - 1; pl[g] = last; }
+            load_vec(buf[g], rdlane(id_lane, last));
+        }
+    }
+
+    __device__ __forceinline__ void reduce(const uint4 (&buf)[GB][NQ], const int (&pl)[GB], float& mine) const {
+        double acc[GB];
+#pragma unroll
+        for (int g = 0; g < GB; ++g) acc[g] = lane_partial(buf[g]);
+        const double tot = fold_sum<GB>(acc, lane);
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+            const double t = __hiloint2double((int)rdlane((u32)__double2hiint(tot), g * (64 / GB)),
+                                              (int)rdlane((u32)__double2loint(tot), g * (64 / GB)));
+            if (lane == pl[g]) mine = (float)t;
+        }
+    }
+
     __device__ __forceinline__ float exact_keys(u32 id_lane, u64 mask) {
         float mine = 0.f;
-        uint4 v[G][NQ];
-        u64 m_issue = mask, m_done = mask;
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            if (m_issue) {
-                const int p = __ffsll((long long)m_issue) - 1;
-                m_issue &= m_issue - 1;
-                load_vec(v[g], rdlane(id_lane, p));
-            }
-        }
-        while (m_done) {
-            double acc[G];
-            int pl[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                acc[g] = 0.0;
-                pl[g] = -1;
-                if (m_done) {
-                    pl[g] = __ffsll((long long)m_done) - 1;
-                    m_done &= m_done - 1;
-                    const double a = lane_partial(v[g]);
-                    acc[g] = a;
-                    if (m_issue) {
-                        const int p = __ffsll((long long)m_issue) - 1;
-                        m_issue &= m_issue - 1;
-                        load_vec(v[g], rdlane(id_lane, p));
-                    }
-                }
-            }
-            const double tot = fold_sum<G>(acc, lane);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                if (pl[g] >= 0) {
-                    const double t = __hiloint2double((int)rdlane((u32)__double2hiint(tot), g * (64 / G)),
-                                                      (int)rdlane((u32)__double2loint(tot), g * (64 / G)));
-                    if (lane == pl[g]) mine = (float)t;
-                }
-            }
+        uint4 va[GB][NQ], vb[GB][NQ];
+        int pa[GB], pb[GB];
+        u64 m = mask;
+        int last = __ffsll((long long)mask) - 1;
+        int left = __popcll(mask);
+        issue(va, pa, m, last, id_lane);
+        for (;;) {
+            // the scheduling barriers keep the requests for one buffer ahead of the arithmetic on the other
+            issue(vb, pb, m, last, id_lane);
+            __builtin_amdgcn_sched_barrier(0);
+            reduce(va, pa, mine);
+            left -= GB;
+            if (left <= 0) break;
+            issue(va, pa, m, last, id_lane);
+            __builtin_amdgcn_sched_barrier(0);
+            reduce(vb, pb, mine);
+            left -= GB;
+            if (left <= 0) break;
         }
         return mine;
     }
