@@ -513,7 +513,7 @@ static void seen_sizes_for(const pag_index* ix, u32 ef, u32 b, u32* hlog, u32* b
         while ((1u << lg) < 2 * expected && lg < 11) ++lg;
         *hlog = lg; *blog = 0;
     } else {
-        *hlog = 9; *blog = 16;
+        *hlog = 9; *blog = 15;
     }
     if (ix->seen_log2) *hlog = ix->seen_log2;
 }

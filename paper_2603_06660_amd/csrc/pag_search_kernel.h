@@ -685,9 +685,9 @@ struct Wave {
 // so long and short searches balance themselves; the loop ends for every wave once the counter
 // passes nq.
 template <int NQ, int NW, bool HALF, int CW>
-#ifdef PAG_WAVES_PER_EU
-__attribute__((amdgpu_waves_per_eu(PAG_WAVES_PER_EU, 8)))
-#endif
+// Short rows leave room for four waves per SIMD (128 VGPRs, a few dwords of spill); longer rows
+// keep their registers for loads in flight.
+__attribute__((amdgpu_waves_per_eu(NQ <= 3 ? 4 : 1, 8)))
 __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x;
