@@ -176,7 +176,8 @@ def main():
     chosen = None
     # the configuration's grid, continued upwards: this synthetic set needs more than efS = 512
     grid = (args.efs,) if args.efs else tuple(w.efs_grid) + tuple(
-        e for e in (640, 768, 896, 1024, 1280, 1536, 1792, 2048, 2560, 3072, 4096) if e > max(w.efs_grid))
+        e for e in (640, 768, 896, 1024, 1152, 1280, 1408, 1536, 1664, 1792, 1920, 2048, 2560, 3072, 4096)
+        if e > max(w.efs_grid))
     for efS in grid:
         ix.reset_counters()
         t1 = time.time()
