@@ -232,10 +232,17 @@ def main():
     k_ms = float(np.mean(kernel_ms))
     achieved = bytes_per_launch / (k_ms * 1e-3) / 1e9
     tag = "cfg%d" % w.cfg if (args.n is None and args.nq is None and not args.fp16_vectors) else "custom"
+    # what this machine delivers when a kernel does nothing but fetch rows of the same vector store
+    rows_probe = min(8 * w.n, 4_000_000)
+    stream_gbs = ix.measure_row_reads(rows_probe, False)
+    gather_gbs = ix.measure_row_reads(rows_probe, True)
+    log("row reads on this box: in order %.0f GB/s, scattered %.0f GB/s" % (stream_gbs, gather_gbs))
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(tag, efS),
                 "kernel": "pagk::k_search", "kernel_ms": round(k_ms, 4), "prepare_ms": round(float(np.mean(prep_ms)), 4),
-                "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+                "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "measured_row_read_GBps": {"in_order": round(stream_gbs, 1), "scattered": round(gather_gbs, 1)},
+                "frac_of_measured_scattered_reads": round(achieved / gather_gbs, 4)}
 
     # ---- CPU oracle on the same index, same efS, bounded sample ----
     cpu = None

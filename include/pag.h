@@ -182,6 +182,14 @@ int pag_screen(const pag_index* ix, const float* tables, uint64_t nq, const uint
 int pag_edge_info(const pag_index* ix, uint64_t node_begin, uint64_t node_end, uint8_t* codes,
                   float* a, float* c, float* e2);
 
+/*
+ * Diagnostic for the roofline (no step of the method): reads `rows` whole rows of the index's vector
+ * store, in order (scattered = 0) or in a scattered permutation (scattered = 1), four rows in flight
+ * per wavefront, and reports the achieved rate in GB/s.  This is what the exact-distance step of
+ * Alg. 2 could reach on this GPU if it did nothing but fetch its vectors.
+ */
+int pag_measure_row_reads(const pag_index* ix, uint64_t rows, int scattered, double* gb_per_s);
+
 const char* pag_last_error(void);
 
 #ifdef __cplusplus

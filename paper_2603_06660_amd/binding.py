@@ -18,7 +18,8 @@ _METRICS = {"l2": L2, "ip": IP, "cos": COS, "cosine": COS, L2: L2, IP: IP, COS: 
 EXPORTED_SYMBOLS = (
     "pag_build", "pag_search", "pag_insert", "pag_free", "pag_describe", "pag_export", "pag_import",
     "pag_get_counters", "pag_reset_counters", "pag_set_search_options", "pag_set_seen_capacity_log2",
-    "pag_prepare_queries", "pag_exact_distances", "pag_screen", "pag_edge_info", "pag_last_error",
+    "pag_prepare_queries", "pag_exact_distances", "pag_screen", "pag_edge_info", "pag_measure_row_reads",
+    "pag_last_error",
 )
 
 
@@ -242,6 +243,13 @@ class PagIndex:
                                          C.c_void_p(u.data_ptr()), _dev_f32(Du, "Du"),
                                          C.c_void_p(est.data_ptr())), "pag_screen")
         return est
+
+    def measure_row_reads(self, rows, scattered):
+        """GB/s at which whole rows of the vector store can be fetched (roofline diagnostic)."""
+        out = C.c_double(0.0)
+        _check(load_library().pag_measure_row_reads(self._h, C.c_uint64(rows), C.c_int(1 if scattered else 0),
+                                                    C.byref(out)), "pag_measure_row_reads")
+        return out.value
 
     def edge_info(self, node_begin, node_end):
         m = self.describe()

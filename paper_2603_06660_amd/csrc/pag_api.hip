@@ -667,3 +667,30 @@ extern "C" int pag_edge_info(const pag_index* cix, uint64_t node_begin, uint64_t
     }
     return PAG_OK;
 }
+
+extern "C" int pag_measure_row_reads(const pag_index* cix, uint64_t rows, int scattered, double* gb_per_s) {
+    pag_index* ix = const_cast<pag_index*>(cix);
+    PAG_CHECK(ix && gb_per_s, PAG_EINVAL, "null argument");
+    PAG_CHECK(rows >= 1 && ix->n >= 1, PAG_EINVAL, "rows must be >= 1");
+    PAG_CHECK(((u64)ix->L.d * (ix->vec_half ? 2 : 4)) % 16 == 0, PAG_EUNSUPPORTED, "rows must be a multiple of 16 bytes");
+    DeviceGuard g(ix->device);
+    // a multiplier coprime with n makes (counter * stride) mod n a permutation of the rows
+    u64 stride = 0;
+    if (scattered) {
+        stride = (u64)(0.6180339887 * (double)ix->n) | 1ull;
+        auto gcd = [](u64 a, u64 b) { while (b) { u64 t = a % b; a = b; b = t; } return a; };
+        while (gcd(stride, ix->n) != 1) stride += 2;
+    }
+    const int grid = ix->num_cu * 16;
+    int rc;
+    for (int rep = 0; rep < 2; ++rep) {      // first pass warms up, second is timed
+        PAG_HIP(hipEventRecord(ix->ev[0], ix->stream));
+        if ((rc = pag_launch_row_reads(ix->stream, ix, rows, stride, ix->d_qcounter + 1, grid))) return rc;
+        PAG_HIP(hipEventRecord(ix->ev[1], ix->stream));
+        PAG_HIP(hipStreamSynchronize(ix->stream));
+    }
+    float ms = 0.f;
+    PAG_HIP(hipEventElapsedTime(&ms, ix->ev[0], ix->ev[1]));
+    *gb_per_s = (double)rows * ix->L.d * (ix->vec_half ? 2 : 4) / ((double)ms * 1e6);
+    return PAG_OK;
+}

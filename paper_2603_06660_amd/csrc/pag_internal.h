@@ -138,6 +138,7 @@ int pag_launch_convert(hipStream_t s, const void* src, u32 src_half, void* dst, 
 int pag_launch_exact(hipStream_t s, const pag_index* ix, const float* qrot, u64 nq, const u32* ids, u32 m, float* keys);
 int pag_launch_screen(hipStream_t s, const pag_index* ix, const float* tables, u64 nq, const u32* u, const float* Du, float* est);
 int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begin, u64 node_end);
+int pag_launch_row_reads(hipStream_t s, const pag_index* ix, u64 rows, u64 stride, u32* sink, int grid);
 int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edge_list, u64 n_edges);
 
 int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid);

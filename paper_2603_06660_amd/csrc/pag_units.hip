@@ -150,6 +150,28 @@ __global__ void __launch_bounds__(64) k_edge_info(pag_vecs V, uint8_t* __restric
     }
 }
 
+// Diagnostic: how fast can this GPU deliver whole rows of the vector store?  Every wave reads rows
+// (four in flight) and folds them into a checksum; `stride` = 0 walks the store in order, otherwise
+// row = (counter * stride) mod n visits it in a scattered order.  No arithmetic of the method.
+__global__ void __launch_bounds__(64) k_row_reads(const uint4* __restrict__ vec, u64 row_chunks, u64 n, u64 rows,
+                                                  u64 stride, u32* __restrict__ sink) {
+    const int lane = threadIdx.x;
+    u32 acc = 0;
+    for (u64 r0 = (u64)blockIdx.x * 4; r0 < rows; r0 += (u64)gridDim.x * 4) {
+        uint4 v[4];
+        u64 row[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) row[g] = stride ? ((r0 + g) * stride) % n : (r0 + g) % n;
+        for (u64 c = lane; c < row_chunks; c += 64) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) v[g] = vec[row[g] * row_chunks + c];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) acc ^= v[g].x ^ v[g].y ^ v[g].z ^ v[g].w;
+        }
+    }
+    if (acc == 0x9E3779B9u) sink[0] = acc;     // practically never: keeps the loads alive
+}
+
 u32 edge_info_lds(const pag_layout& L) { return 2 * L.d * 4 + 2 * L.P * 8 + L.Ppad * 4; }
 
 }  // namespace
@@ -194,6 +216,14 @@ int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edg
     if (n_edges == 0) return PAG_OK;
     hipLaunchKernelGGL(k_edge_info, dim3((unsigned)n_edges), dim3(64), edge_info_lds(ix->L), s, pag_vecs_of(ix), ix->rec,
                        ix->e2, ix->L, ix->cb, edge_list, n_edges, 0ull);
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
+}
+
+int pag_launch_row_reads(hipStream_t s, const pag_index* ix, u64 rows, u64 stride, u32* sink, int grid) {
+    const u64 row_chunks = (u64)ix->L.d * (ix->vec_half ? 2 : 4) / 16;
+    hipLaunchKernelGGL(k_row_reads, dim3((unsigned)grid), dim3(64), 0, s, (const uint4*)ix->vec, row_chunks, ix->n, rows,
+                       stride, sink);
     PAG_HIP(hipGetLastError());
     return PAG_OK;
 }
