@@ -118,7 +118,7 @@ def main():
     ap.add_argument("--cfg", type=int, default=2)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--nq", type=int, default=None)
-    ap.add_argument("--efc", type=int, default=1000)
+    ap.add_argument("--efc", type=int, default=2000)
     ap.add_argument("--efs", type=int, default=0, help="skip the sweep and time this efS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
