@@ -21,6 +21,8 @@
  *     returns a thread-local, human readable description of the last failure.
  *     No exception crosses this boundary.
  *   - Node ids are the row numbers of the vectors in insertion order.
+ *   - A handle owns workspaces and counters: calls on one index must not overlap in time
+ *     (different indexes are independent).
  */
 #ifndef PAG_H
 #define PAG_H

@@ -636,23 +636,19 @@ extern "C" int pag_edge_info(const pag_index* cix, uint64_t node_begin, uint64_t
     const pag_layout& L = ix->L;
     const u64 m = node_end - node_begin;
     // work on a scratch copy of the records so that the index itself is left untouched
-    pag_index tmp = *ix;
+    uint8_t* srec = nullptr;
+    float* se2 = nullptr;
     int rc;
-    if ((rc = dev_alloc(&tmp.rec, m * L.rec_bytes))) return rc;
-    if ((rc = dev_alloc(&tmp.e2, m * L.deg))) { (void)hipFree(tmp.rec); return rc; }
+    if ((rc = dev_alloc(&srec, m * L.rec_bytes))) return rc;
+    if ((rc = dev_alloc(&se2, m * L.deg))) { (void)hipFree(srec); return rc; }
     std::vector<uint8_t> buf(m * L.rec_bytes);
     std::vector<float> he2(m * L.deg);
-    hipError_t e = hipMemcpyAsync(tmp.rec, ix->rec + node_begin * L.rec_bytes, m * L.rec_bytes, hipMemcpyDeviceToDevice, ix->stream);
-    // the kernel addresses records and e2 by absolute node id: shift the bases
-    tmp.rec -= node_begin * L.rec_bytes;
-    tmp.e2 -= node_begin * L.deg;
-    if (e == hipSuccess) rc = pag_launch_edge_info_nodes(ix->stream, &tmp, node_begin, node_end);
-    tmp.rec += node_begin * L.rec_bytes;
-    tmp.e2 += node_begin * L.deg;
+    hipError_t e = hipMemcpyAsync(srec, ix->rec + node_begin * L.rec_bytes, m * L.rec_bytes, hipMemcpyDeviceToDevice, ix->stream);
+    if (e == hipSuccess) rc = pag_launch_edge_info_nodes(ix->stream, ix, node_begin, node_end, srec, se2, node_begin);
     if (e == hipSuccess && rc == PAG_OK) e = hipStreamSynchronize(ix->stream);
-    if (e == hipSuccess && rc == PAG_OK) e = hipMemcpy(buf.data(), tmp.rec, buf.size(), hipMemcpyDeviceToHost);
-    if (e == hipSuccess && rc == PAG_OK) e = hipMemcpy(he2.data(), tmp.e2, he2.size() * 4, hipMemcpyDeviceToHost);
-    (void)hipFree(tmp.rec); (void)hipFree(tmp.e2);
+    if (e == hipSuccess && rc == PAG_OK) e = hipMemcpy(buf.data(), srec, buf.size(), hipMemcpyDeviceToHost);
+    if (e == hipSuccess && rc == PAG_OK) e = hipMemcpy(he2.data(), se2, he2.size() * 4, hipMemcpyDeviceToHost);
+    (void)hipFree(srec); (void)hipFree(se2);
     if (rc) return rc;
     if (e != hipSuccess) { pag_set_error(std::string("pag_edge_info: ") + hipGetErrorString(e)); return PAG_EHIP; }
     for (u64 i = 0; i < m; ++i) {

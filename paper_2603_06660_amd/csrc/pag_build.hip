@@ -15,7 +15,6 @@
 
 #include "pag_internal.h"
 
-int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid);
 
 namespace {
 
@@ -282,7 +281,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
             const u32 lds = L.d * 4 + 2 * n_init * 8;
             hipLaunchKernelGGL(k_init_clique, dim3(n_init), dim3(64), lds, s, pag_vecs_of(ix), ix->rec, L, n_init);
             PAG_HIP(hipGetLastError());
-            if ((rc = pag_launch_edge_info_nodes(s, ix, 0, n_init))) return rc;
+            if ((rc = pag_launch_edge_info_nodes(s, ix, 0, n_init, ix->rec, ix->e2, 0))) return rc;
         }
         pos = n_init;
         // the search kernel reads entry ids from device memory: ids 0 .. min(n, 1024) - 1
@@ -368,7 +367,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
                            ws.rv_out, n_pairs, ws.edges, ws.n_edges);
         PAG_HIP(hipGetLastError());
         // 6. inference information of the new forward edges and of every changed reverse slot
-        if ((rc = pag_launch_edge_info_nodes(s, ix, pos, pos + m))) return rc;
+        if ((rc = pag_launch_edge_info_nodes(s, ix, pos, pos + m, ix->rec, ix->e2, 0))) return rc;
         u32 n_edges = 0;
         PAG_HIP(hipMemcpyAsync(&n_edges, ws.n_edges, 4, hipMemcpyDeviceToHost, s));
         PAG_HIP(hipStreamSynchronize(s));

@@ -137,7 +137,9 @@ int pag_launch_zero_u32(hipStream_t s, u32* p, u64 count);
 int pag_launch_convert(hipStream_t s, const void* src, u32 src_half, void* dst, u32 dst_half, u64 count);   // float <-> __half, round to nearest even
 int pag_launch_exact(hipStream_t s, const pag_index* ix, const float* qrot, u64 nq, const u32* ids, u32 m, float* keys);
 int pag_launch_screen(hipStream_t s, const pag_index* ix, const float* tables, u64 nq, const u32* u, const float* Du, float* est);
-int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begin, u64 node_end);
+// recomputes every slot of nodes [node_begin, node_end) into records / e2 rows that start at node out_base
+int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begin, u64 node_end, uint8_t* recs,
+                               float* e2, u64 out_base);
 int pag_launch_row_reads(hipStream_t s, const pag_index* ix, u64 rows, u64 stride, u32* sink, int grid);
 int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edge_list, u64 n_edges);
 

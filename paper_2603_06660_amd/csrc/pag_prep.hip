@@ -107,7 +107,7 @@ __global__ void __launch_bounds__(64) k_normalise(const float* __restrict__ X, u
     for (u32 k = lane; k < d; k += 64) out[row * d + k] = (float)((double)x[k] / nrm);
 }
 
-// float -> __half (round to nearest even) or __half -> float (exact), 4 elements per thread
+// float -> __half (round to nearest even) or __half -> float (exact), one element per thread
 __global__ void __launch_bounds__(256) k_convert(const void* __restrict__ src, u32 src_half, void* __restrict__ dst,
                                                  u32 dst_half, u64 count) {
     const u64 i = (u64)blockIdx.x * 256 + threadIdx.x;

@@ -1,5 +1,5 @@
 // PRT-TFB best-first search (Alg. 2, Sec. 3.3): one wavefront owns one query from the
-// entry nodes to the final top-K.  Included by the per-NQ instantiation units.
+// entry nodes to the final top-K.  Included by the instantiation units pag_search_nq*_cw*.hip.
 //
 // Wave-level data placement (64 lanes):
 //   query        registers, NQ float4 per lane (element chunk c*64+lane)
@@ -7,7 +7,8 @@
 //   R_L          registers, same placement (capacity K <= b)
 //   table T      LDS, float [Ppad][16]
 //   seen set     LDS open-addressing hash of node ids (exact); overflows into a per-wave HBM bitmap
-//   R_F, R_T     LDS rings of b keys each
+//                that an LDS Bloom filter guards
+//   R_F, R_T     LDS rings (power-of-two buffers, the last b pushes are valid)
 //   SA, SB       LDS scratch for scatters and rank sorts
 // A key packs (dist bits << 32) | (id << 1) | visited, so that unsigned comparison orders by
 // (dist, id); distances are sums of squares, hence non-negative and monotone as bit patterns.

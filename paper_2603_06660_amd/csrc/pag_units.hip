@@ -71,11 +71,12 @@ __global__ void __launch_bounds__(64) k_screen(const uint8_t* __restrict__ recs,
 //   codes[l] = argmax_j <r_jl, (w-u)_l>  (ties -> smallest j), k ascending fp64 sums
 //   e2 = ||w-u||^2, maxsum = sum_l best_l, off = sum_l <u_l, r*_l>  (l ascending)
 //   a = ||w-u|| / max(maxsum/||w-u||, 1e-6), c = e2 + 2 a off; both 0 when w == u
-// Lane l owns subspace l (l, l+64, ...).  Results go straight into the adjacency record and e2.
+// Lane l owns subspace l (l, l+64, ...).  Results go straight into the adjacency record and e2;
+// `recs` and `e2_out` start at node `out_base` (0 for the index itself, or a scratch copy of a range).
 __global__ void __launch_bounds__(64) k_edge_info(pag_vecs V, uint8_t* __restrict__ recs,
                                                   float* __restrict__ e2_out, pag_layout L,
                                                   const float* __restrict__ cb, const u32* __restrict__ edges,
-                                                  u64 n_edges, u64 node_begin) {
+                                                  u64 n_edges, u64 node_begin, u64 out_base) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* diff = (float*)smem;               // [d]
     float* uu = diff + L.d;                   // [d]
@@ -92,14 +93,15 @@ __global__ void __launch_bounds__(64) k_edge_info(pag_vecs V, uint8_t* __restric
         u = (u32)(node_begin + blockIdx.x / L.deg);
         slot = blockIdx.x % L.deg;
     }
-    uint8_t* rec = recs + (u64)u * L.rec_bytes;
+    uint8_t* rec = recs + ((u64)u - out_base) * L.rec_bytes;
+    float* e2_row = e2_out + ((u64)u - out_base) * L.deg;
     const u32 w = ((const u32*)rec)[slot];
     u32* cw_out = (u32*)(rec + L.off_codes) + slot * L.cw;
     if (w == PAG_EMPTY) {
         if (lane == 0) {
             ((float*)(rec + L.off_a))[slot] = 0.f;
             ((float*)(rec + L.off_c))[slot] = 0.f;
-            e2_out[(u64)u * L.deg + slot] = 0.f;
+            e2_row[slot] = 0.f;
         }
         if ((u32)lane < L.cw) cw_out[lane] = 0u;
         return;
@@ -146,7 +148,7 @@ __global__ void __launch_bounds__(64) k_edge_info(pag_vecs V, uint8_t* __restric
         }
         ((float*)(rec + L.off_a))[slot] = (float)a;
         ((float*)(rec + L.off_c))[slot] = (float)c;
-        e2_out[(u64)u * L.deg + slot] = (float)e2;
+        e2_row[slot] = (float)e2;
     }
 }
 
@@ -195,7 +197,8 @@ int pag_launch_screen(hipStream_t s, const pag_index* ix, const float* tables, u
     return PAG_OK;
 }
 
-int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begin, u64 node_end) {
+int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begin, u64 node_end, uint8_t* recs,
+                               float* e2, u64 out_base) {
     if (node_end <= node_begin) return PAG_OK;
     const u64 total = (node_end - node_begin) * ix->L.deg;
     const u64 step = 1ull << 30;
@@ -206,7 +209,7 @@ int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begi
         const u64 ne = nb + nodes_per < node_end ? nb + nodes_per : node_end;
         if (nb >= node_end) break;
         hipLaunchKernelGGL(k_edge_info, dim3((unsigned)((ne - nb) * ix->L.deg)), dim3(64), edge_info_lds(ix->L), s,
-                           pag_vecs_of(ix), ix->rec, ix->e2, ix->L, ix->cb, (const u32*)nullptr, 0ull, nb);
+                           pag_vecs_of(ix), recs, e2, ix->L, ix->cb, (const u32*)nullptr, 0ull, nb, out_base);
     }
     PAG_HIP(hipGetLastError());
     return PAG_OK;
@@ -215,7 +218,7 @@ int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begi
 int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edge_list, u64 n_edges) {
     if (n_edges == 0) return PAG_OK;
     hipLaunchKernelGGL(k_edge_info, dim3((unsigned)n_edges), dim3(64), edge_info_lds(ix->L), s, pag_vecs_of(ix), ix->rec,
-                       ix->e2, ix->L, ix->cb, edge_list, n_edges, 0ull);
+                       ix->e2, ix->L, ix->cb, edge_list, n_edges, 0ull, 0ull);
     PAG_HIP(hipGetLastError());
     return PAG_OK;
 }
