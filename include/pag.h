@@ -49,7 +49,7 @@ typedef enum {
 /*
  * Index parameters (Alg. 1 inputs; Appendix D).  Names in brackets are the
  * paper's.  Limits of this build: d % 4 == 0, d <= 3072, num_subspaces <= 64,
- * d % num_subspaces == 0, max_degree <= 64, working-set size b <= 128.
+ * d % num_subspaces == 0, max_degree <= 64, working-set size b <= 1024.
  */
 typedef struct {
     uint32_t struct_size;     /* sizeof(pag_params), for ABI checking */

@@ -143,7 +143,7 @@ int check_params(const pag_params* p) {
     PAG_CHECK(p->struct_size == sizeof(pag_params), PAG_EINVAL, "pag_params.struct_size does not match this library");
     PAG_CHECK(p->metric >= PAG_L2 && p->metric <= PAG_COS, PAG_EINVAL, "unknown metric");
     PAG_CHECK(p->ef_construction >= 1, PAG_EINVAL, "ef_construction must be >= 1");
-    PAG_CHECK(p->search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 128 is not built");
+    PAG_CHECK(p->search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 1024 is not built");
     return PAG_OK;
 }
 
@@ -473,7 +473,7 @@ extern "C" int pag_reset_counters(pag_index* ix) {
 
 extern "C" int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t flags) {
     PAG_CHECK(ix, PAG_EINVAL, "null argument");
-    PAG_CHECK(search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 128 is not built");
+    PAG_CHECK(search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 1024 is not built");
     ix->search_b = search_b;
     ix->flags = (ix->flags & PAG_FLAG_NO_PES) | (flags & PAG_FLAG_NO_PRT);   // index-time bits stay as built
     return PAG_OK;
@@ -505,7 +505,7 @@ static int prepare(pag_index* ix, const float* Q, u64 nq, float* qrot, float* ta
 // Seen-set sizing.  First level: an exact LDS hash.  A search expected to compute at most ~1000
 // exact distances (entries + a few per visited node) gets a hash that holds all of them.  Longer
 // searches get a small hash for the early nodes, and behind it the per-wave HBM bitmap guarded by
-// an 8 KB LDS Bloom filter: large LDS tables cost more in occupancy than the bitmap costs in loads.
+// a 4 KB LDS Bloom filter: large LDS tables cost more in occupancy than the bitmap costs in loads.
 static void seen_sizes_for(const pag_index* ix, u32 ef, u32 b, u32* hlog, u32* blog) {
     const u32 expected = b + 8 * std::max(ef, b);
     if (expected <= 1024) {
@@ -532,6 +532,7 @@ int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, 
     a->flags = ix->flags;
     a->qcounter = ix->d_qcounter; a->counters = ix->d_counters;
     *lds = (u32)pag_search_lds_bytes(L, b, a->hlog, a->blog, a);
+    if (*lds > 65536) { pag_set_error("search: working set, tables and seen set need more than 64 KB of LDS per wave"); return PAG_EUNSUPPORTED; }
     int rc = pag_search_max_grid(ix, b, *lds, grid);
     if (rc) return rc;
     // per-wave spill bitmaps of the seen set: one bit per node, rounded to 16 bytes
@@ -557,7 +558,7 @@ extern "C" int pag_search(const pag_index* cix, const float* Q, uint64_t nq, uin
     PAG_CHECK(nq < (1ull << 31), PAG_EINVAL, "nq must be below 2^31");
     const u32 b = ix->search_b ? ix->search_b : std::max<u32>(10, K);
     PAG_CHECK(b >= K, PAG_EINVAL, "search_b must be >= K");
-    PAG_CHECK(b <= PAG_MAX_B, PAG_EUNSUPPORTED, "working sets above 128 nodes (K > 128) are not built");
+    PAG_CHECK(b <= PAG_MAX_B, PAG_EUNSUPPORTED, "working sets above 1024 nodes (K > 1024) are not built");
     DeviceGuard g(ix->device);
     const pag_layout& L = ix->L;
     int rc;

@@ -15,7 +15,8 @@ typedef uint32_t u32;
 #define PAG_EMPTY 0xFFFFFFFFu
 #define PAG_NCODE 16        // projection vectors per subspace (Appendix D (1)): one code is 4 bits
 #define PAG_KEY_INVALID 0xFFFFFFFFFFFFFFFFull
-#define PAG_MAX_B 128       // working-set size limit: two entries per lane
+#define PAG_MAX_B 1024      // working-set size limit: sixteen entries per lane
+#define PAG_RANK_SORT_MAX 256  // lists up to this length are sorted by ranks, longer ones by a bitonic network
 #define PAG_MAX_DEG 64      // one neighbour per lane
 #define PAG_MAX_CW 8        // code dwords per neighbour: up to 64 subspaces
 
@@ -111,7 +112,7 @@ struct SearchArgs {
     u32 d, deg, Ppad, cw, rec_bytes, off_a, off_c, off_codes;
     u32 nq, K, b, Rmax, hlog, blog, flags;   // hlog: log2 slots of the LDS hash; blog: log2 bits of the Bloom filter (0 = none)
     u32 off_hash, off_bloom, off_sa, off_sb, off_rf, off_rt;   // LDS offsets (bytes)
-    u32 ring_mask;           // rings live in power-of-two buffers of >= 2b slots; only the last b pushes are valid
+    u32 ring_mask;           // rings live in power-of-two buffers of >= b slots; only the last b pushes are valid
     long long* out_ids;      // [nq * K]       (search mode)
     float* out_dists;        // [nq * K]
     float out_scale;         // 1 for L2, 0.5 for IP / COS

@@ -2,7 +2,7 @@
 // carve-up and the persistent grid.
 #include "pag_internal.h"
 
-typedef void (*pag_search_fn)(const SearchArgs);
+typedef void (*pag_search_fn)(const SearchArgs);   // selectors: one per (row chunks per lane, code dwords)
 pag_search_fn pag_search_fn_nq1_cw2(int, bool);
 pag_search_fn pag_search_fn_nq1_cw4(int, bool);
 pag_search_fn pag_search_fn_nq1_cw8(int, bool);
@@ -26,7 +26,8 @@ pag_search_fn pag_search_fn_nq12_cw4(int, bool);
 pag_search_fn pag_search_fn_nq12_cw8(int, bool);
 
 static pag_search_fn pick(u32 d, u32 b, bool half, u32 cw) {
-    const int nw = b <= 64 ? 1 : 2;
+    int nw = 1;                                       // entries of W per lane: 64 * nw >= b
+    while (64u * nw < b) nw *= 2;
     const u32 per_chunk_row = half ? 512 : 256;       // elements covered by one 16-byte chunk per lane
     const u32 chunks = (d + per_chunk_row - 1) / per_chunk_row;
 #define PAG_PICK_CW(NQ)                                              \
@@ -54,10 +55,18 @@ int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, u32 blog, SearchA
     u32 off = align_up(L.Ppad * PAG_NCODE * 4, 16);
     a->off_hash = off; off += (4u << hlog);
     a->off_bloom = off; off += blog ? (1u << blog) / 8 : 0;
-    a->off_sa = off;   off += align_up(2 * b * 8, 16);
-    a->off_sb = off;   off += align_up(2 * b * 8, 16);
-    u32 ring = 32;
-    while (ring < 2 * b) ring *= 2;
+    // round ends sort up to 2b keys: by ranks from SA into SB, or, for long lists, in place in SA
+    // padded to a power of two
+    u32 sa = 2 * b, sb = 2 * b;
+    if (2 * b > PAG_RANK_SORT_MAX) {
+        sa = 64;
+        while (sa < 2 * b) sa *= 2;
+        sb = 0;
+    }
+    a->off_sa = off;   off += align_up(sa * 8, 16);
+    a->off_sb = off;   off += align_up(sb * 8, 16);
+    u32 ring = 32;                                    // the last b pushes must stay apart: any power of two >= b
+    while (ring < b) ring *= 2;
     a->ring_mask = ring - 1;
     a->off_rf = off;   off += ring * 8;
     a->off_rt = off;   off += ring * 8;

@@ -3,13 +3,13 @@
 //
 // Wave-level data placement (64 lanes):
 //   query        registers, NQ float4 per lane (element chunk c*64+lane)
-//   W            registers, sorted ascending by key; rank r lives in slot r/64 of lane r%64
+//   W            registers, sorted ascending by key; rank r lives in slot r/64 of lane r%64 (NW slots, b <= 64 NW)
 //   R_L          registers, same placement (capacity K <= b)
 //   table T      LDS, float [Ppad][16]
 //   seen set     LDS open-addressing hash of node ids (exact); overflows into a per-wave HBM bitmap
 //                that an LDS Bloom filter guards
 //   R_F, R_T     LDS rings (power-of-two buffers, the last b pushes are valid)
-//   SA, SB       LDS scratch for scatters and rank sorts
+//   SA, SB       LDS scratch for scatters and sorts (SB only for working sets of up to 128 nodes)
 // A key packs (dist bits << 32) | (id << 1) | visited, so that unsigned comparison orders by
 // (dist, id); distances are sums of squares, hence non-negative and monotone as bit patterns.
 //
@@ -120,7 +120,7 @@ __device__ __forceinline__ void bloom_set(u32* B, u32 blog, u32 id) {
     atomicOr(&B[h2 >> 5], 1u << (h2 & 31));
 }
 
-// dst[rank] = src[i], rank = number of smaller keys; keys are distinct.  n <= 4 * 64.
+// dst[rank] = src[i], rank = number of smaller keys; keys are distinct.  Quadratic: for short lists.
 __device__ __forceinline__ void rank_sort(const u64* src, u64* dst, u32 n, int lane) {
     for (u32 i = lane; i < n; i += 64) {
         const u64 k = src[i];
@@ -128,6 +128,38 @@ __device__ __forceinline__ void rank_sort(const u64* src, u64* dst, u32 n, int l
         for (u32 j = 0; j < n; ++j) r += (src[j] < k) ? 1u : 0u;
         dst[r] = k;
     }
+}
+
+// In-place ascending bitonic sort of S[0, n) by one wave; S has room for n rounded up to a power
+// of two (the tail is padded with the largest key).
+__device__ __forceinline__ void bitonic_sort(u64* S, u32 n, int lane) {
+    u32 N = 64;
+    while (N < n) N <<= 1;
+    for (u32 i = n + lane; i < N; i += 64) S[i] = PAG_KEY_INVALID;
+    lds_sync();
+    for (u32 k = 2; k <= N; k <<= 1)
+        for (u32 j = k >> 1; j > 0; j >>= 1) {
+            for (u32 t = lane; t < N / 2; t += 64) {
+                const u32 i = ((t & ~(j - 1)) << 1) | (t & (j - 1));   // bit j clear
+                const u32 l = i | j;
+                const u64 x = S[i], y = S[l];
+                if ((x > y) == ((i & k) == 0)) { S[i] = y; S[l] = x; }
+            }
+            lds_sync();
+        }
+}
+
+// Sorts the n keys in `a` ascending and returns where the result lives.  Working sets whose lists
+// are always short (by_ranks) go through the rank sort into `b`; the others sort in place, and
+// their `b` does not exist.
+__device__ __forceinline__ const u64* sort_keys(u64* a, u64* b, u32 n, bool by_ranks, int lane) {
+    if (by_ranks) {
+        rank_sort(a, b, n, lane);
+        lds_sync();
+        return b;
+    }
+    bitonic_sort(a, n, lane);
+    return a;
 }
 
 // Optional per-phase timers (diagnostic builds only): every mark first drains all outstanding
@@ -399,8 +431,10 @@ struct Wave {
             u32 c = 0;
 #pragma unroll
             for (int s = 0; s < NW; ++s) {
-                c += (u32)__popcll(__ballot(W[s] < k));
-                cntW[s] += (k < W[s]) ? 1u : 0u;
+                // keys are distinct, so one comparison tells both sides (an empty slot counts as larger)
+                const bool lt = W[s] < k;
+                c += (u32)__popcll(__ballot(lt));
+                cntW[s] += lt ? 0u : 1u;
             }
             cP += (k < pk) ? 1u : 0u;
             if (lane == p) cPW = c;
@@ -604,13 +638,12 @@ struct Wave {
                 }
                 lds_sync();
                 const u32 n = nRL + nW;
-                rank_sort(SA, SB, n, lane);
-                lds_sync();
+                const u64* S = sort_keys(SA, SB, n, 2 * b <= PAG_RANK_SORT_MAX, lane);
                 nRL = n < A.K ? n : A.K;
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
                     const u32 idx = s * 64 + lane;
-                    RL[s] = idx < nRL ? SB[idx] : PAG_KEY_INVALID;
+                    RL[s] = idx < nRL ? S[idx] : PAG_KEY_INVALID;
                 }
                 lds_sync();
             }
@@ -619,16 +652,15 @@ struct Wave {
                 for (u32 i = lane; i < cntT; i += 64) SA[cntF + i] = RT[(hdT - cntT + i) & A.ring_mask];
                 lds_sync();
                 const u32 n = cntF + cntT;
-                rank_sort(SA, SB, n, lane);
-                lds_sync();
+                const u64* S = sort_keys(SA, SB, n, 2 * b <= PAG_RANK_SORT_MAX, lane);
                 nW = n < b ? n : b;
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
                     const u32 idx = s * 64 + lane;
-                    W[s] = idx < nW ? SB[idx] : PAG_KEY_INVALID;
+                    W[s] = idx < nW ? S[idx] : PAG_KEY_INVALID;
                 }
                 const u32 rest = n - nW;                         // <= b; written worst first
-                for (u32 j = lane; j < rest; j += 64) RT[j] = SB[n - 1 - j];
+                for (u32 j = lane; j < rest; j += 64) RT[j] = S[n - 1 - j];
                 cntT = rest; hdT = rest;
                 cntF = 0; hdF = 0;
                 lds_sync();
@@ -688,7 +720,7 @@ struct Wave {
 template <int NQ, int NW, bool HALF, int CW>
 // Short rows leave room for four waves per SIMD (128 VGPRs, a few dwords of spill); longer rows
 // keep their registers for loads in flight.
-__attribute__((amdgpu_waves_per_eu(NQ <= 3 ? 4 : 1, 8)))
+__attribute__((amdgpu_waves_per_eu(NQ <= 3 && NW <= 2 ? 4 : 1, 8)))
 __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x;
@@ -705,3 +737,21 @@ __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
 
 }  // namespace pagk
 
+// One translation unit per (NQ, CW) defines the selector below: the kernels for every number of
+// W / R_L entries per lane (working sets of up to 64, 128, 256, 512, 1024 nodes) and both stores.
+typedef void (*pag_search_fn)(const SearchArgs);
+#define PAG_SEARCH_INSTANCES(NQ, CW)                                                                  \
+    template <bool HALF>                                                                              \
+    static pag_search_fn pag_search_by_nw(int nw) {                                                   \
+        switch (nw) {                                                                                 \
+            case 1: return (pag_search_fn)pagk::k_search<NQ, 1, HALF, CW>;                            \
+            case 2: return (pag_search_fn)pagk::k_search<NQ, 2, HALF, CW>;                            \
+            case 4: return (pag_search_fn)pagk::k_search<NQ, 4, HALF, CW>;                            \
+            case 8: return (pag_search_fn)pagk::k_search<NQ, 8, HALF, CW>;                            \
+            case 16: return (pag_search_fn)pagk::k_search<NQ, 16, HALF, CW>;                          \
+            default: return nullptr;                                                                  \
+        }                                                                                             \
+    }                                                                                                 \
+    pag_search_fn pag_search_fn_nq##NQ##_cw##CW(int nw, bool half) {                                  \
+        return half ? pag_search_by_nw<true>(nw) : pag_search_by_nw<false>(nw);                       \
+    }

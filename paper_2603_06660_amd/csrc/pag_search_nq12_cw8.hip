@@ -2,8 +2,4 @@
 // (fp32 rows of up to 3072 elements, 16-bit rows of up to 6144), 8 code dwords per neighbour.
 #include "pag_search_kernel.h"
 
-typedef void (*pag_search_fn)(const SearchArgs);
-pag_search_fn pag_search_fn_nq12_cw8(int nw, bool half) {
-    if (half) return nullptr;
-    return nw == 1 ? (pag_search_fn)pagk::k_search<12, 1, false, 8> : (pag_search_fn)pagk::k_search<12, 2, false, 8>;
-}
+PAG_SEARCH_INSTANCES(12, 8)

@@ -2,8 +2,4 @@
 // (fp32 rows of up to 768 elements, 16-bit rows of up to 1536), 4 code dwords per neighbour.
 #include "pag_search_kernel.h"
 
-typedef void (*pag_search_fn)(const SearchArgs);
-pag_search_fn pag_search_fn_nq3_cw4(int nw, bool half) {
-    if (half) return nw == 1 ? (pag_search_fn)pagk::k_search<3, 1, true, 4> : (pag_search_fn)pagk::k_search<3, 2, true, 4>;
-    return nw == 1 ? (pag_search_fn)pagk::k_search<3, 1, false, 4> : (pag_search_fn)pagk::k_search<3, 2, false, 4>;
-}
+PAG_SEARCH_INSTANCES(3, 4)

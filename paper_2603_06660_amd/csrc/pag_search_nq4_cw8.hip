@@ -2,8 +2,4 @@
 // (fp32 rows of up to 1024 elements, 16-bit rows of up to 2048), 8 code dwords per neighbour.
 #include "pag_search_kernel.h"
 
-typedef void (*pag_search_fn)(const SearchArgs);
-pag_search_fn pag_search_fn_nq4_cw8(int nw, bool half) {
-    if (half) return nw == 1 ? (pag_search_fn)pagk::k_search<4, 1, true, 8> : (pag_search_fn)pagk::k_search<4, 2, true, 8>;
-    return nw == 1 ? (pag_search_fn)pagk::k_search<4, 1, false, 8> : (pag_search_fn)pagk::k_search<4, 2, false, 8>;
-}
+PAG_SEARCH_INSTANCES(4, 8)

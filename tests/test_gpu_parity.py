@@ -148,6 +148,25 @@ def test_large_k_two_entries_per_lane(orc, cfg1_small, cfg1_oracle_index, import
     _assert_search_parity(imported, cfg1_oracle_index, q[:40], 50, 128)
 
 
+@pytest.mark.parametrize("K,efS,b", [(200, 400, 0), (129, 129, 0), (500, 700, 0), (1000, 1000, 0), (1000, 2500, 0),
+                                     (10, 512, 512), (10, 900, 300), (64, 1024, 1024)])
+def test_large_working_sets(orc, cfg1_small, cfg1_oracle_index, imported, K, efS, b):
+    """Retrieval sizes up to K = 1000 (Sec. 5, demand D5): W and R_L take 4, 8 or 16 register slots per
+    lane and round ends sort up to 2b keys with the bitonic network; b = efS is the single-pool mode."""
+    w, base, q, gt, gtk = cfg1_small
+    gtK, _ = wl.brute_force(base, q[:48], K, w.metric)
+    try:
+        imported.set_search_options(search_b=b, flags=0)
+        imported.reset_counters()
+        gi, gd, oc = _assert_search_parity(imported, cfg1_oracle_index, q[:48], K, efS, gtK, b=b)
+        gc = imported.counters()
+        for k_g, k_o in (("hops", "hops"), ("tests", "tests"), ("passes", "passes"), ("exact", "exact"),
+                         ("rounds", "rounds"), ("rf_overflow", "rf_over"), ("rt_overflow", "rt_over")):
+            assert gc[k_g] == oc[k_o], (k_g, gc[k_g], oc[k_o])
+    finally:
+        imported.set_search_options(0, 0)
+
+
 def test_working_set_override_and_no_prt(orc, cfg1_small, cfg1_oracle_index, imported):
     """search_b = efS (one pool, one round) and the test switched off: textbook best-first search."""
     w, base, q, gt, gtk = cfg1_small
