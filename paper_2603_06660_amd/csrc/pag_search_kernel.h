@@ -55,32 +55,41 @@ __device__ __forceinline__ double row16_sum(double x) {
     return x;
 }
 
+// x' + y' after exchanging the upper half of x with the lower half of y (HALF32), or the odd
+// 16-lane rows of x with the even rows of y: lanes of the lower half (even rows) end up with
+// x[l] + x[partner], the others with y[partner] + y[l].  gfx950's lane-swap instructions do this
+// without LDS traffic.
+template <bool HALF32>
+__device__ __forceinline__ double swap_add(double x, double y) {
+    const u32 xl = (u32)__double2loint(x), xh = (u32)__double2hiint(x);
+    const u32 yl = (u32)__double2loint(y), yh = (u32)__double2hiint(y);
+    if constexpr (HALF32) {
+        const auto lo = __builtin_amdgcn_permlane32_swap(xl, yl, false, false);
+        const auto hi = __builtin_amdgcn_permlane32_swap(xh, yh, false, false);
+        return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+    } else {
+        const auto lo = __builtin_amdgcn_permlane16_swap(xl, yl, false, false);
+        const auto hi = __builtin_amdgcn_permlane16_swap(xh, yh, false, false);
+        return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+    }
+}
+
 // Sums of G per-lane partials over the wave at once: the cross-row steps fold the G values
-// onto the four rows (each lane keeps the partials of "its" value and hands the others over),
-// the in-row steps are DPP.  Afterwards every lane of row r holds the total of value
-// r * G / 4 (G = 4), r / 2 (G = 2) or 0 (G = 1).
+// onto the four rows, the in-row steps are DPP.  Afterwards every lane of row r holds the
+// total of value r (G = 4), r / 2 (G = 2) or 0 (G = 1).
 template <int G>
-__device__ __forceinline__ double fold_sum(const double (&acc)[G], int lane) {
+__device__ __forceinline__ double fold_sum(const double* acc) {
     double k;
     if constexpr (G == 4) {
-        const bool h32 = lane & 32, h16 = lane & 16;
-        double k0 = h32 ? acc[2] : acc[0], k1 = h32 ? acc[3] : acc[1];
-        const double s0 = h32 ? acc[0] : acc[2], s1 = h32 ? acc[1] : acc[3];
-        k0 += __shfl_xor(s0, 32, 64);
-        k1 += __shfl_xor(s1, 32, 64);
-        k = h16 ? k1 : k0;
-        const double sx = h16 ? k0 : k1;
-        k += __shfl_xor(sx, 16, 64);
+        const double k0 = swap_add<true>(acc[0], acc[2]);   // lower half: value 0, upper half: value 2
+        const double k1 = swap_add<true>(acc[1], acc[3]);   //             value 1,             value 3
+        k = swap_add<false>(k0, k1);
     } else if constexpr (G == 2) {
-        const bool h32 = lane & 32;
-        k = h32 ? acc[1] : acc[0];
-        const double sx = h32 ? acc[0] : acc[1];
-        k += __shfl_xor(sx, 32, 64);
-        k += __shfl_xor(k, 16, 64);
+        k = swap_add<true>(acc[0], acc[1]);
+        k = swap_add<false>(k, k);
     } else {
-        k = acc[0];
-        k += __shfl_xor(k, 32, 64);
-        k += __shfl_xor(k, 16, 64);
+        k = swap_add<true>(acc[0], acc[0]);
+        k = swap_add<false>(k, k);
     }
     return row16_sum(k);
 }
@@ -177,9 +186,12 @@ __device__ __forceinline__ const u64* sort_keys(u64* a, u64* b, u32 n, bool by_r
 #endif
 
 // S = sum_l T[l][code_l] over the CW * 8 subspaces of one neighbour, added in increasing l.
-// The LDS gathers of 16 subspaces are issued together, then consumed in order.
+// The LDS gathers of 16 subspaces are issued together, then consumed in order.  `t_base` is the
+// LDS byte address of T, a multiple of 64, so that "4 * code" can be OR-ed into it and the row
+// offset 64 * l rides in the instruction.
+typedef __attribute__((address_space(3))) const float* lds_cfloat_ptr;
 template <int CW>
-__device__ __forceinline__ float table_sum(const float* T, const u32 (&cwv)[CW]) {
+__device__ __forceinline__ float table_sum(u32 t_base, const u32 (&cwv)[CW]) {
     float S = 0.f;
 #pragma unroll
     for (int k = 0; k < CW; k += 2) {
@@ -187,7 +199,9 @@ __device__ __forceinline__ float table_sum(const float* T, const u32 (&cwv)[CW])
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const u32 wd = cwv[k + j / 8];
-            t[j] = T[(k * 8 + j) * PAG_NCODE + ((wd >> (4 * (j % 8))) & 15u)];
+            const int sh = 4 * (j % 8) - 2;
+            const u32 x = sh < 0 ? wd << 2 : wd >> sh;
+            t[j] = ((lds_cfloat_ptr)(uintptr_t)((x & 60u) | t_base))[(k * 8 + j) * PAG_NCODE];
         }
 #pragma unroll
         for (int j = 0; j < 16; ++j) S = S + t[j];
@@ -204,6 +218,7 @@ struct Wave {
     const SearchArgs A;
     const int lane;
     float* T;
+    u32 t_base;                     // LDS byte address of T
     u32* H;
     u32* BL;
     u64 *SA, *SB, *RF, *RT;
@@ -232,6 +247,7 @@ struct Wave {
 
     __device__ Wave(const SearchArgs& a, unsigned char* smem, int ln) : A(a), lane(ln) {
         T = (float*)smem;
+        t_base = (u32)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
         H = (u32*)(smem + a.off_hash);
         BL = (u32*)(smem + a.off_bloom);
         SA = (u64*)(smem + a.off_sa);
@@ -249,26 +265,26 @@ struct Wave {
 #endif
     }
 
-    // lane s < deg reads neighbour slot s of node u: id, a, c and its chunk of 4-bit codes
+    // lane s < deg reads neighbour slot s of node u: id, a, c and its chunk of 4-bit codes.  The
+    // other lanes read slot 0 and get an empty id (their a, c and codes are never used), so the
+    // loads sit in straight-line code and can stay in flight across whatever follows.
     __device__ __forceinline__ void load_record(u32 u, u32& id, float& ea, float& ec, u32 (&cwv)[CW]) const {
         const uint8_t* rec = A.rec + (u64)u * A.rec_bytes;
-        id = PAG_EMPTY; ea = 0.f; ec = 0.f;
+        const bool in = (u32)lane < A.deg;
+        const u32 sl = in ? (u32)lane : 0u;
+        const u32 raw = ((const u32*)rec)[sl];
+        id = in ? raw : PAG_EMPTY;
+        ea = ((const float*)(rec + A.off_a))[sl];
+        ec = ((const float*)(rec + A.off_c))[sl];
+        const u32* cp = (const u32*)(rec + A.off_codes) + sl * CW;   // 16-byte aligned section
+        if constexpr (CW == 2) {
+            const uint2 t = *(const uint2*)cp;
+            cwv[0] = t.x; cwv[1] = t.y;
+        } else {
 #pragma unroll
-        for (int k = 0; k < CW; ++k) cwv[k] = 0;
-        if ((u32)lane < A.deg) {
-            id = ((const u32*)rec)[lane];
-            ea = ((const float*)(rec + A.off_a))[lane];
-            ec = ((const float*)(rec + A.off_c))[lane];
-            const u32* cp = (const u32*)(rec + A.off_codes) + (u32)lane * CW;   // 16-byte aligned section
-            if constexpr (CW == 2) {
-                const uint2 t = *(const uint2*)cp;
-                cwv[0] = t.x; cwv[1] = t.y;
-            } else {
-#pragma unroll
-                for (int k = 0; k < CW; k += 4) {
-                    const uint4 t = *(const uint4*)(cp + k);
-                    cwv[k] = t.x; cwv[k + 1] = t.y; cwv[k + 2] = t.z; cwv[k + 3] = t.w;
-                }
+            for (int k = 0; k < CW; k += 4) {
+                const uint4 t = *(const uint4*)(cp + k);
+                cwv[k] = t.x; cwv[k + 1] = t.y; cwv[k + 2] = t.z; cwv[k + 3] = t.w;
             }
         }
     }
@@ -359,7 +375,7 @@ struct Wave {
         double acc[GB];
 #pragma unroll
         for (int g = 0; g < GB; ++g) acc[g] = lane_partial(buf[g]);
-        const double tot = fold_sum<GB>(acc, lane);
+        const double tot = fold_sum<GB>(acc);
 #pragma unroll
         for (int g = 0; g < GB; ++g) {
             const double t = __hiloint2double((int)rdlane((u32)__double2hiint(tot), g * (64 / GB)),
@@ -593,7 +609,7 @@ struct Wave {
                 if (!(A.flags & PAG_FLAG_NO_PRT)) {
                     float S = 0.f;
                     if (cand || (want_pes && in_graph)) {
-                        S = table_sum<CW>(T, cwv);
+                        S = table_sum<CW>(t_base, cwv);
                     }
                     est = __builtin_fmaf(-2.0f * ea, S, Du + ec);
                 }
@@ -722,7 +738,7 @@ template <int NQ, int NW, bool HALF, int CW>
 // keep their registers for loads in flight.
 __attribute__((amdgpu_waves_per_eu(NQ <= 3 && NW <= 2 ? 4 : 1, 8)))
 __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
-    extern __shared__ __align__(16) unsigned char smem[];
+    extern __shared__ __align__(64) unsigned char smem[];   // the table sits first: see table_sum
     const int lane = threadIdx.x;
     Wave<NQ, NW, HALF, CW> w(A, smem, lane);
     for (;;) {
