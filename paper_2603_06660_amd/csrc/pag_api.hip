@@ -254,7 +254,7 @@ extern "C" int pag_free(pag_index* ix) {
     DeviceGuard g(ix->device);
     (void)hipStreamSynchronize(ix->stream);
     void* ptrs[] = { ix->vec, ix->rec, ix->e2, ix->rot, ix->cb, ix->entry, ix->ws_qrot, ix->ws_tab, ix->ws_norm,
-                     ix->ws_bitmap, ix->d_qcounter, ix->d_counters };
+                     ix->ws_bitmap, ix->ws_rings, ix->d_qcounter, ix->d_counters };
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (auto& e : ix->ev) if (e) (void)hipEventDestroy(e);
     delete ix;
@@ -544,6 +544,10 @@ int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, 
         PAG_HIP(hipMemsetAsync(ix->ws_bitmap, 0, need * 4, ix->stream));
     }
     a->bitmap = ix->ws_bitmap;
+    if (b > PAG_LDS_RING_MAX_B) {
+        if ((rc = ensure_ws(&ix->ws_rings, &ix->ws_rings_cap, (u64)*grid * 2 * (a->ring_mask + 1)))) return rc;
+        a->rings = ix->ws_rings;
+    }
     return PAG_OK;
 }
 

@@ -17,6 +17,7 @@ typedef uint32_t u32;
 #define PAG_KEY_INVALID 0xFFFFFFFFFFFFFFFFull
 #define PAG_MAX_B 1024      // working-set size limit: sixteen entries per lane
 #define PAG_RANK_SORT_MAX 256  // lists up to this length are sorted by ranks, longer ones by a bitonic network
+#define PAG_LDS_RING_MAX_B 128  // larger working sets keep R_F / R_T in HBM (the kernel's NW > 2 instantiations)
 #define PAG_MAX_DEG 64      // one neighbour per lane
 #define PAG_MAX_CW 8        // code dwords per neighbour: up to 64 subspaces
 
@@ -94,6 +95,7 @@ struct pag_index {
     float* ws_tab;   u64 ws_tab_cap;      // floats
     float* ws_norm;  u64 ws_norm_cap;     // floats (normalised copies for COS)
     u32* ws_bitmap;  u64 ws_bitmap_cap;   // u32 words: per-wave seen-set spill bitmaps
+    u64* ws_rings;   u64 ws_rings_cap;    // u64 keys: per-wave R_F / R_T of large working sets
     u32* d_qcounter;                      // persistent-wave work counter
     u64* d_counters;                      // CTR_COUNT
     hipEvent_t ev[4];
@@ -113,6 +115,7 @@ struct SearchArgs {
     u32 nq, K, b, Rmax, hlog, blog, flags;   // hlog: log2 slots of the LDS hash; blog: log2 bits of the Bloom filter (0 = none)
     u32 off_hash, off_bloom, off_sa, off_sb, off_rf, off_rt;   // LDS offsets (bytes)
     u32 ring_mask;           // rings live in power-of-two buffers of >= b slots; only the last b pushes are valid
+    u64* rings;              // [grid * 2 * (ring_mask + 1)] per-wave R_F, R_T when b > PAG_LDS_RING_MAX_B, else unused
     long long* out_ids;      // [nq * K]       (search mode)
     float* out_dists;        // [nq * K]
     float out_scale;         // 1 for L2, 0.5 for IP / COS

@@ -68,8 +68,9 @@ int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, u32 blog, SearchA
     u32 ring = 32;                                    // the last b pushes must stay apart: any power of two >= b
     while (ring < b) ring *= 2;
     a->ring_mask = ring - 1;
-    a->off_rf = off;   off += ring * 8;
-    a->off_rt = off;   off += ring * 8;
+    const u32 ring_lds = b > PAG_LDS_RING_MAX_B ? 0 : ring * 8;   // above that the rings live in HBM
+    a->off_rf = off;   off += ring_lds;
+    a->off_rt = off;   off += ring_lds;
     return (int)off;
 }
 

@@ -8,7 +8,9 @@
 //   table T      LDS, float [Ppad][16]
 //   seen set     LDS open-addressing hash of node ids (exact); overflows into a per-wave HBM bitmap
 //                that an LDS Bloom filter guards
-//   R_F, R_T     LDS rings (power-of-two buffers, the last b pushes are valid)
+//   R_F, R_T     rings (power-of-two buffers, the last b pushes are valid): LDS, or per-wave HBM
+//                buffers for working sets above 128 nodes, which are pushed to rarely and read
+//                once per round
 //   SA, SB       LDS scratch for scatters and sorts (SB only for working sets of up to 128 nodes)
 // A key packs (dist bits << 32) | (id << 1) | visited, so that unsigned comparison orders by
 // (dist, id); distances are sums of squares, hence non-negative and monotone as bit patterns.
@@ -225,6 +227,7 @@ struct Wave {
     u32* bitmap;
     // per query
     static constexpr int QV = HALF ? 2 * NQ : NQ;   // float4 registers holding the query
+    static constexpr bool RINGS_IN_HBM = NW > 2;    // matches the host's LDS carve-up
     float4 q[QV];
     u64 W[NW];
     u64 RL[NW];
@@ -252,8 +255,13 @@ struct Wave {
         BL = (u32*)(smem + a.off_bloom);
         SA = (u64*)(smem + a.off_sa);
         SB = (u64*)(smem + a.off_sb);
-        RF = (u64*)(smem + a.off_rf);
-        RT = (u64*)(smem + a.off_rt);
+        if constexpr (RINGS_IN_HBM) {
+            RF = a.rings + (u64)blockIdx.x * 2 * (a.ring_mask + 1);
+            RT = RF + (a.ring_mask + 1);
+        } else {
+            RF = (u64*)(smem + a.off_rf);
+            RT = (u64*)(smem + a.off_rt);
+        }
         bitmap = a.bitmap + (u64)blockIdx.x * a.bitmap_words;
         const bool tail_ok = ((NQ - 1) * 64 + (u32)ln) * (HALF ? 8u : 4u) < a.d;
         tail_idx = tail_ok ? (NQ - 1) * 64 + (u32)ln : 0u;
@@ -664,6 +672,8 @@ struct Wave {
                 lds_sync();
             }
             {
+                // rings in HBM: this wave's own pushes (by other lanes) must have landed before they are read
+                if constexpr (RINGS_IN_HBM) __threadfence();
                 for (u32 i = lane; i < cntF; i += 64) SA[i] = RF[(hdF - cntF + i) & A.ring_mask];
                 for (u32 i = lane; i < cntT; i += 64) SA[cntF + i] = RT[(hdT - cntT + i) & A.ring_mask];
                 lds_sync();
