@@ -199,6 +199,12 @@ def main():
         chosen = (curve[-1]["efS"], curve[-1]["recall"])
         log("recall %.2f not reached on the grid; timing the largest efS" % TARGET_RECALL)
     efS, recall = chosen
+    # linear interpolation between the two grid points that bracket the target (single-call rates)
+    interp = None
+    for lo, hi in zip(curve, curve[1:]):
+        if lo["recall"] < TARGET_RECALL <= hi["recall"] and hi["efS"] == efS:
+            t = (TARGET_RECALL - lo["recall"]) / (hi["recall"] - lo["recall"])
+            interp = round(lo["qps_single_call"] + t * (hi["qps_single_call"] - lo["qps_single_call"]), 1)
 
     if args.pmc_probe:
         x = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
@@ -261,9 +267,15 @@ def main():
         oi, od, oc = oix.search(q[:sample], w.K, efS, threads=cores)
         dt = time.perf_counter() - t2
         agree = float((oi == ids[:sample].cpu().numpy()).mean())
+        # the paper's own convention is one thread: a few seconds of that as well
+        n1 = int(max(4, min(sample, 4.0 / max(per_q * cores, 1e-9))))
+        t2 = time.perf_counter()
+        oix.search(q[:n1], w.K, efS, threads=1)
+        dt1 = time.perf_counter() - t2
         cpu = {"value": round(sample / dt, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
                "sample": "first %d of %d queries, same exported index, efS=%d; id-slot agreement with the GPU %.5f"
-                         % (sample, w.nq, efS, agree)}
+                         % (sample, w.nq, efS, agree),
+               "single_thread": {"value": round(n1 / dt1, 1), "unit": "queries/s", "sample": "first %d queries" % n1}}
         log("cpu oracle: %.1f QPS on %d threads over %d queries; GPU/oracle id agreement %.5f" %
             (sample / dt, cores, sample, agree))
 
@@ -276,6 +288,7 @@ def main():
                                (w.cfg, w.name, w.n, w.d, w.nq, w.K, w.deg, w.P, args.efc),
                    "efS": efS, "efS_within_configured_grid": bool(efS <= max(w.efs_grid)),
                    "recall_at_K": round(recall, 4), "recall_target_reached": reached,
+                   "qps_interpolated_at_recall_%.2f" % TARGET_RECALL: interp,
                    "skipped_fraction": round(1.0 - c["passes"] / max(1, c["tests"]), 4),
                    "hops_per_query": round(c["hops"] / max(1, c["queries"]), 1),
                    "exact_per_query": round(c["exact"] / max(1, c["queries"]), 1),
