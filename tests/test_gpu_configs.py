@@ -74,6 +74,28 @@ def test_other_workload_shapes(orc, cfg, n, nq, efC, efS):
     assert np.allclose(gd, 1.0 - ip, atol=5e-6)
 
 
+@pytest.mark.parametrize("cfg,n,K,efS,fp16", [(3, 20000, 300, 600, False), (4, 12000, 200, 400, True),
+                                               (5, 8000, 1000, 1000, False)])
+def test_large_retrieval_sizes_at_workload_shapes(orc, cfg, n, K, efS, fp16):
+    """K = 200 .. 1000 (4, 8, 16 register slots per lane, rings in HBM) at the other workloads' row
+    lengths, degrees and code widths, on an fp32 and on a 16-bit store."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_FP16_VECTORS
+    w = wl.workload(cfg, n=n, nq=64)
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    metric = {0: "l2", 1: "ip", 2: "cos"}[w.metric]
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric=metric, max_degree=w.deg, num_subspaces=w.P,
+                         ef_construction=100, seed=cfg, flags=FLAG_FP16_VECTORS if fp16 else 0)
+    ex = gix.export()
+    oix = _oracle_view(orc, ex)
+    gt, _ = wl.brute_force(base, q, K, w.metric)
+    gix.reset_counters()
+    gi, gd, oi = _parity(orc, gix, oix, q, K, efS)
+    assert abs(wl.recall_at_k(gi, gt) - wl.recall_at_k(oi, gt)) <= 0.002
+    assert wl.recall_at_k(gi, gt) >= 0.8
+    assert np.all(np.diff(gd, axis=1) >= 0)
+
+
 def test_online_insertion_rounds(orc):
     """Workload 5's structure at reduced size: insertion batches interleaved with query batches."""
     PagIndex = _gpu()
