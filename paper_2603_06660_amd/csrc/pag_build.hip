@@ -14,7 +14,7 @@
 #include <vector>
 
 #include "pag_internal.h"
-
+#include "pag_wave.h"
 
 namespace {
 
@@ -37,6 +37,30 @@ __device__ __forceinline__ float dist_lds(const pag_vecs& V, u32 d, const float*
         acc = __builtin_fma((double)dw, (double)dw, acc);
     }
     return (float)wave_sum(acc);
+}
+
+// squared distances between the vector staged in LDS and four rows at once (their loads are in
+// flight together); all lanes get all four results
+__device__ __forceinline__ void dist_lds4(const pag_vecs& V, u32 d, const float* s, const u32 (&id)[4], float (&out)[4]) {
+    const float4* q = (const float4*)s;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (u32 c = threadIdx.x; c < d / 4; c += 64) {
+        const float4 a = q[c];
+        float4 b[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) b[g] = pag_vload4(V, id[g], c);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float dx = a.x - b[g].x, dy = a.y - b[g].y, dz = a.z - b[g].z, dw = a.w - b[g].w;
+            acc[g] = __builtin_fma((double)dx, (double)dx, acc[g]);
+            acc[g] = __builtin_fma((double)dy, (double)dy, acc[g]);
+            acc[g] = __builtin_fma((double)dz, (double)dz, acc[g]);
+            acc[g] = __builtin_fma((double)dw, (double)dw, acc[g]);
+        }
+    }
+    const double tot = pagk::fold_sum<4>(acc);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) out[g] = (float)pagk::fold_total<4>(tot, g);
 }
 
 __device__ __forceinline__ void stage(const pag_vecs& V, u32 d, u32 id, float* s, int lane) {
@@ -78,15 +102,17 @@ __global__ void __launch_bounds__(64) k_init_clique(pag_vecs vec, uint8_t* __res
 // pair per kept neighbour: key = target << 32 | dist bits, value = v.
 __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restrict__ recs,
                                                   pag_layout L, u32 node0, u32 m, const u64* __restrict__ cand,
-                                                  const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
+                                                  u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
                                                   const u64* __restrict__ pes,
                                                   u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sv = (float*)smem;                  // [d] candidate vector
-    u64* sorted = (u64*)(sv + L.d);            // [cand_cap]
-    u32* kept = (u32*)(sorted + cand_cap);     // [deg]
+    u32* kept = (u32*)(sv + L.d);              // [deg]
     const u32 vi = blockIdx.x;
     if (vi >= m) return;
+    // the sorted list lives in HBM: it is read once, front to back, and keeping it out of LDS lets
+    // four times as many waves hide each other's row-fetch latency
+    u64* sorted = cand_sorted + (u64)vi * cand_cap;
     const int lane = threadIdx.x;
     const u32 v = node0 + vi;
     const u64* mine = cand + (u64)vi * cand_cap;
@@ -98,6 +124,7 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
         for (u32 j = 0; j < nc; ++j) r += ((mine[j] & ~1ull) < k) ? 1u : 0u;
         sorted[r] = k;
     }
+    __threadfence();           // entries written by other lanes of this wave are read below
     __syncthreads();
     if (nc > efC) nc = efC;
     u32 nk = 0;
@@ -110,9 +137,14 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
         stage(vec, L.d, c, sv, lane);
         __syncthreads();
         bool occluded = false;
-        for (u32 s = 0; s < nk && !occluded; ++s) {
-            const float dsc = dist_lds(vec, L.d, sv, kept[s], lane);
-            occluded = dsc <= dvc;
+        for (u32 s0 = 0; s0 < nk && !occluded; s0 += 4) {
+            u32 sid[4];
+            float dsc[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) sid[g] = kept[s0 + g < nk ? s0 + g : nk - 1];
+            dist_lds4(vec, L.d, sv, sid, dsc);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) occluded = occluded || dsc[g] <= dvc;   // a repeated last entry changes nothing
         }
         if (!occluded) {
             if ((u32)lane == nk) { my_id = c; my_key = (u32)(k >> 32); kept[nk] = c; }
@@ -248,12 +280,12 @@ __global__ void __launch_bounds__(64) k_reverse(pag_vecs vec, uint8_t* __restric
 }
 
 struct BuildWs {
-    u64* cand = nullptr; u32* cand_cnt = nullptr; u64* pes = nullptr;
+    u64* cand = nullptr; u64* cand_sorted = nullptr; u32* cand_cnt = nullptr; u64* pes = nullptr;
     u64 *rk_in = nullptr, *rk_out = nullptr; u32 *rv_in = nullptr, *rv_out = nullptr;
     u32* edges = nullptr; u32* n_edges = nullptr;
     void* sort_tmp = nullptr; size_t sort_bytes = 0;
     ~BuildWs() {
-        void* p[] = { cand, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, sort_tmp };
+        void* p[] = { cand, cand_sorted, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, sort_tmp };
         for (void* x : p) if (x) (void)hipFree(x);
     }
 };
@@ -295,6 +327,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     u64 max_batch = ix->subbatch ? ix->subbatch : std::min<u64>(16384, std::max<u64>(1024, n_end / 50));
     BuildWs ws;
     PAG_ALLOC(ws.cand, max_batch * cand_cap * 8);
+    PAG_ALLOC(ws.cand_sorted, max_batch * cand_cap * 8);
     PAG_ALLOC(ws.cand_cnt, max_batch * 4);
     const bool use_pes = !(ix->flags & PAG_FLAG_NO_PES);
     if (use_pes) PAG_ALLOC(ws.pes, max_batch * L.deg * 8);
@@ -352,9 +385,9 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
         // 3. RobustPrune -> N_out(v), reverse pairs
         {
-            const u32 plds = L.d * 4 + cand_cap * 8 + L.deg * 4;
+            const u32 plds = L.d * 4 + L.deg * 4;
             hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, (u32)pos, (u32)m,
-                               ws.cand, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
+                               ws.cand, ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
             PAG_HIP(hipGetLastError());
         }
         // 4. group reverse pairs by target
