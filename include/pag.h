@@ -149,7 +149,9 @@ int pag_free(pag_index* ix);
 int pag_describe(const pag_index* ix, pag_arrays* out);
 /* Copies the index into the caller-allocated host arrays of `out` (sizes as reported by pag_describe). */
 int pag_export(const pag_index* ix, pag_arrays* out);
-/* Creates an index from host arrays (all of them required); params gives capacity, efC, search_b, seed, stream. */
+/* Creates an index from host arrays (all of them required); params gives capacity, efC, search_b, seed, stream.
+ * The graph is validated on the host: PAG_EINVAL for a neighbour or entry id >= n, a code above 15, a neighbour
+ * listed twice by one node, or an entry id listed twice. */
 int pag_import(const pag_arrays* in, const pag_params* params, pag_index** out);
 
 int pag_get_counters(const pag_index* ix, pag_counters* out);

@@ -391,7 +391,18 @@ extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_in
     const u64 n = in->n;
     for (u64 i = 0; i < n * L.deg; ++i)
         PAG_CHECK(in->adj[i] == PAG_EMPTY || in->adj[i] < n, PAG_EINVAL, "pag_import: neighbour id out of range");
-    for (u32 i = 0; i < in->n_entry; ++i) PAG_CHECK(in->entry[i] < n, PAG_EINVAL, "pag_import: entry id out of range");
+    // the search admits the unseen neighbours of a node together and relies on their keys being
+    // distinct: a node may not list a neighbour twice, nor the entry list a node twice
+    for (u64 u = 0; u < n; ++u) {
+        const u32* row = in->adj + u * L.deg;
+        for (u32 i = 1; i < L.deg; ++i)
+            for (u32 j = 0; j < i; ++j)
+                PAG_CHECK(row[i] == PAG_EMPTY || row[i] != row[j], PAG_EINVAL, "pag_import: a node lists a neighbour twice");
+    }
+    for (u32 i = 0; i < in->n_entry; ++i) {
+        PAG_CHECK(in->entry[i] < n, PAG_EINVAL, "pag_import: entry id out of range");
+        for (u32 j = 0; j < i; ++j) PAG_CHECK(in->entry[i] != in->entry[j], PAG_EINVAL, "pag_import: entry id listed twice");
+    }
     for (u64 i = 0; i < n * L.deg * L.P; ++i) PAG_CHECK(in->codes[i] < PAG_NCODE, PAG_EINVAL, "pag_import: code above 15");
     PAG_CHECK(!(params->flags & PAG_FLAG_FP16_VECTORS) || in->d % 8 == 0, PAG_EUNSUPPORTED,
               "PAG_FLAG_FP16_VECTORS needs d % 8 == 0");

@@ -209,6 +209,17 @@ def test_edge_cases(orc):
     _assert_search_parity(gix, oix, q, 10, 57)
     with pytest.raises(PagError):
         PagIndex.build(torch.zeros((10, 30), device="cuda"), num_subspaces=4)      # d % P != 0
+    # imported graphs are validated: ids in range, no neighbour listed twice, distinct entry ids
+    for breakage in ("range", "twice", "entry"):
+        adj, entry = oix.adj.copy(), oix.entry.copy()
+        if breakage == "range":
+            adj[3, 0] = 500
+        elif breakage == "twice":
+            adj[3, 1] = adj[3, 0]
+        else:
+            entry[1] = entry[0]
+        with pytest.raises(PagError):
+            PagIndex.from_arrays(oix.vec, adj, oix.a, oix.c, oix.e2, oix.codes, oix.rot, oix.cb, entry, metric="l2")
 
 
 def test_cosine_and_ip(orc):
