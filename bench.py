@@ -76,7 +76,16 @@ def online_insertion(args, w, wl, torch, np, PagIndex):
                         seed=2603, capacity=cap)
     build_s = time.time() - t0
     log("pag_build of the initial %d vectors: %.2f s" % (w.n, build_s))
-    efS = args.efs or 512
+    # efS: the smallest of a grid that reaches the recall target on the initial index, then kept
+    efS = args.efs
+    if not efS:
+        gt0, _ = wl.brute_force_torch(all_d[:w.n], q_d, w.K, w.metric)
+        for efS in (128, 256, 512, 768, 1024, 1536, 2048, 3072, 4096):
+            ids, _ = ix.search(q_d, w.K, efS)
+            rec0 = wl.recall_at_k(ids.cpu().numpy(), gt0)
+            log("initial index: efS %4d recall@%d %.4f" % (efS, w.K, rec0))
+            if rec0 >= TARGET_RECALL:
+                break
     n = w.n
     rows = []
     ins_time = 0.0
