@@ -238,3 +238,47 @@ def test_pes_adds_edges_only_to_free_slots(orc, cfg1_small):
     r0 = wl.recall_at_k(plain.search(q, w.K, 32)[0], gt15)
     r1 = wl.recall_at_k(full.search(q, w.K, 32)[0], gt15)
     assert r1 >= r0 - 0.01
+
+
+def _read_hand_trace():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "tfb_hand_trace.txt")
+    common, cases, cur = {}, [], None
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        if line.startswith("["):
+            cur = {}
+            cases.append(cur)
+            continue
+        key, val = line.split(":", 1)
+        (common if cur is None else cur)[key.strip()] = val.strip()
+    return common, cases
+
+
+def test_hand_traced_tfb_rounds(orc):
+    """Alg. 2's round mechanics (eviction to R_T, false positives to R_F, FIFO overflow, refill of W with
+    visited flags kept, termination) against traces worked out by hand: tests/golden/tfb_hand_trace.txt."""
+    common, cases = _read_hand_trace()
+    pos = np.array(common["positions"].split(), dtype=np.float32)
+    n, b, K = len(pos), int(common["b"]), int(common["K"])
+    vec = np.zeros((n, 2), np.float32)
+    vec[:, 0] = pos
+    deg, P = 2, 1
+    assert cases
+    for case in cases:
+        adj = np.full((n, deg), orc.EMPTY, np.uint32)
+        for item in case["adjacency"].split():
+            u, nb = item.split(":")
+            nb = [int(x) for x in nb.split(",")]
+            adj[int(u), :len(nb)] = nb
+        ix = orc.OracleIndex(vec, adj, np.zeros((n, deg), np.float32), np.zeros((n, deg), np.float32),
+                             np.zeros((n, deg), np.float32), np.zeros((n, deg, P), np.uint8),
+                             np.eye(2, dtype=np.float32), orc.make_codebooks(2, P, 1),
+                             np.arange(n, dtype=np.uint32))
+        ids, dists, ctr = ix.search(np.zeros((1, 2), np.float32), K, int(case["efS"]), b=b, flags=orc.NO_PRT)
+        assert ids[0].tolist() == [int(x) for x in case["ids"].split()]
+        assert dists[0].tolist() == [float(x) for x in case["dists"].split()]
+        for key in ("hops", "exact", "tests", "passes", "rounds", "rt_over", "rf_over"):
+            assert ctr[key] == int(case[key]), (key, ctr[key], case[key])
