@@ -22,7 +22,9 @@
  *     No exception crosses this boundary.
  *   - Node ids are the row numbers of the vectors in insertion order.
  *   - A handle owns workspaces and counters: calls on one index must not overlap in time
- *     (different indexes are independent).
+ *     (different indexes are independent).  The exception is a pag_searcher, which has
+ *     workspaces, counters and a stream of its own: pag_searcher_search may run while
+ *     pag_insert, pag_search or other searchers work on the same index.
  */
 #ifndef PAG_H
 #define PAG_H
@@ -193,6 +195,27 @@ int pag_edge_info(const pag_index* ix, uint64_t node_begin, uint64_t node_end, u
  * Alg. 2 could reach on this GPU if it did nothing but fetch its vectors.
  */
 int pag_measure_row_reads(const pag_index* ix, uint64_t rows, int scattered, double* gb_per_s);
+
+/*
+ * Searchers: searching while the index grows (the online-insertion setting of Sec. 5.2, D6).
+ * A searcher is a view of an index with its own workspaces, counters and stream (a hipStream_t;
+ * pass one that does not synchronise with the index's stream, else the calls just take turns).
+ * pag_searcher_search is pag_search on that view: it sees the nodes whose insertion had completed when
+ * the call began (pag_insert publishes its nodes after its last kernel has finished); nodes being inserted
+ * are invisible.  While an insertion rewrites the out-edges of older nodes, a search may read an edge's
+ * neighbour id and its inference information from different moments; that can change which neighbours
+ * are tested in that hop, never a reported id/distance pair, which always comes from the stored vectors.
+ * Results are therefore valid but, during an insertion, not reproducible bit for bit.
+ * One searcher serves one call at a time; any number of searchers may share an index.  Free the
+ * searchers before the index.  search_b, flags and the seen-set option are read from the index at each call.
+ * For callers that insert and query at the same time from different host threads.
+ */
+typedef struct pag_searcher pag_searcher;
+int pag_searcher_create(const pag_index* ix, void* stream, pag_searcher** out);
+int pag_searcher_search(pag_searcher* s, const float* Q, uint64_t nq, uint32_t K, uint32_t efS,
+                        int64_t* ids, float* dists);
+int pag_searcher_get_counters(const pag_searcher* s, pag_counters* out);
+int pag_searcher_free(pag_searcher* s);
 
 const char* pag_last_error(void);
 

@@ -19,6 +19,7 @@ EXPORTED_SYMBOLS = (
     "pag_build", "pag_search", "pag_insert", "pag_free", "pag_describe", "pag_export", "pag_import",
     "pag_get_counters", "pag_reset_counters", "pag_set_search_options", "pag_set_seen_capacity_log2",
     "pag_prepare_queries", "pag_exact_distances", "pag_screen", "pag_edge_info", "pag_measure_row_reads",
+    "pag_searcher_create", "pag_searcher_search", "pag_searcher_get_counters", "pag_searcher_free",
     "pag_last_error",
 )
 
@@ -172,6 +173,10 @@ class PagIndex:
     def insert(self, X):
         _check(load_library().pag_insert(self._h, _dev_f32(X, "X"), C.c_uint64(X.shape[0])), "pag_insert")
 
+    def searcher(self, stream=None):
+        """A PagSearcher on this index: searches on its own stream that may overlap with insert()."""
+        return PagSearcher(self, stream)
+
     # ---- support -------------------------------------------------------
     def describe(self):
         arr = _Arrays(C.sizeof(_Arrays))
@@ -261,3 +266,48 @@ class PagIndex:
         _check(load_library().pag_edge_info(self._h, C.c_uint64(node_begin), C.c_uint64(node_end), _np_ptr(codes),
                                             _np_ptr(a), _np_ptr(c), _np_ptr(e2)), "pag_edge_info")
         return codes, a, c, e2
+
+
+class PagSearcher:
+    """pag_searcher: a view of an index with its own workspaces, counters and stream."""
+
+    def __init__(self, index, stream=None):
+        import torch
+        self._index = index              # keeps the index alive: searchers are freed first
+        self._stream = stream if stream is not None else torch.cuda.Stream()
+        h = C.c_void_p()
+        _check(load_library().pag_searcher_create(index._h, C.c_void_p(self._stream.cuda_stream), C.byref(h)),
+               "pag_searcher_create")
+        self._h = h
+
+    def search(self, queries, K, efS, out=None):
+        import torch
+        nq = queries.shape[0]
+        if out is None:
+            with torch.cuda.stream(self._stream):
+                ids = torch.empty((nq, K), dtype=torch.int64, device=queries.device)
+                dists = torch.empty((nq, K), dtype=torch.float32, device=queries.device)
+        else:
+            ids, dists = out
+        _check(load_library().pag_searcher_search(self._h, _dev_f32(queries, "queries"), C.c_uint64(nq), C.c_uint32(K),
+                                                  C.c_uint32(efS), C.c_void_p(ids.data_ptr()),
+                                                  C.c_void_p(dists.data_ptr())), "pag_searcher_search")
+        return ids, dists
+
+    def counters(self):
+        c = _Counters(C.sizeof(_Counters))
+        _check(load_library().pag_searcher_get_counters(self._h, C.byref(c)), "pag_searcher_get_counters")
+        out = {k: getattr(c, k) for k, _ in c._fields_ if k not in ("struct_size", "phase_cycles")}
+        out["phase_cycles"] = list(c.phase_cycles)
+        return out
+
+    def close(self):
+        if self._h is not None and self._h.value:
+            load_library().pag_searcher_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

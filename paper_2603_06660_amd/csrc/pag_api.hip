@@ -306,7 +306,8 @@ extern "C" int pag_insert(pag_index* ix, const float* X, uint64_t m) {
     int rc;
     if ((rc = ingest(ix, X, m, ix->n))) return rc;
     if ((rc = pag_build_range(ix, ix->n, ix->n + m))) return rc;
-    ix->n += m;
+    // publish: every kernel of the insertion has finished (pag_build_range synchronises), searchers may now see the nodes
+    __atomic_store_n(&ix->n, ix->n + m, __ATOMIC_RELEASE);
     if ((rc = set_entry_list(ix))) return rc;
     ix->last_build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     return PAG_OK;
@@ -562,10 +563,10 @@ int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, 
     return PAG_OK;
 }
 
-extern "C" int pag_search(const pag_index* cix, const float* Q, uint64_t nq, uint32_t K, uint32_t efS,
-                          int64_t* ids, float* dists) {
-    pag_index* ix = const_cast<pag_index*>(cix);   // workspaces and counters are mutable state of the handle
-    PAG_CHECK(ix != nullptr, PAG_EINVAL, "index is null");
+// The search of one batch with the workspaces, counters, events and stream of `ix` (an index, or a
+// searcher's view of one).
+static int search_impl(pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uint32_t efS, int64_t* ids,
+                       float* dists) {
     if (nq == 0) return PAG_OK;
     PAG_CHECK(Q && ids && dists, PAG_EINVAL, "Q, ids or dists is null");
     PAG_CHECK(K >= 1 && K <= ix->n, PAG_EINVAL, "K must be in 1..n");
@@ -597,6 +598,83 @@ extern "C" int pag_search(const pag_index* cix, const float* Q, uint64_t nq, uin
     float ms = 0.f;
     PAG_HIP(hipEventElapsedTime(&ms, ix->ev[0], ix->ev[1])); ix->last_prepare_ms = ms;
     PAG_HIP(hipEventElapsedTime(&ms, ix->ev[1], ix->ev[2])); ix->last_search_ms = ms;
+    return PAG_OK;
+}
+
+extern "C" int pag_search(const pag_index* cix, const float* Q, uint64_t nq, uint32_t K, uint32_t efS,
+                          int64_t* ids, float* dists) {
+    pag_index* ix = const_cast<pag_index*>(cix);   // workspaces and counters are mutable state of the handle
+    PAG_CHECK(ix != nullptr, PAG_EINVAL, "index is null");
+    return search_impl(ix, Q, nq, K, efS, ids, dists);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Searchers: a view of an index with workspaces, counters, events and a stream of its own, so that
+// searches can run while pag_insert (or another searcher) works on the same index.
+struct pag_searcher {
+    pag_index view;             // shares the parent's HBM-resident index, owns everything else
+    const pag_index* parent;
+};
+
+static void searcher_release(pag_searcher* s) {
+    pag_index& v = s->view;
+    void* ptrs[] = { v.ws_qrot, v.ws_tab, v.ws_norm, v.ws_bitmap, v.ws_rings, v.d_qcounter, v.d_counters };
+    for (void* p : ptrs) if (p) (void)hipFree(p);
+    for (auto& e : v.ev) if (e) (void)hipEventDestroy(e);
+    delete s;
+}
+
+extern "C" int pag_searcher_create(const pag_index* ix, void* stream, pag_searcher** out) {
+    PAG_CHECK(out != nullptr, PAG_EINVAL, "out is null");
+    *out = nullptr;
+    PAG_CHECK(ix != nullptr, PAG_EINVAL, "index is null");
+    DeviceGuard g(ix->device);
+    pag_searcher* s = new pag_searcher();
+    s->parent = ix;
+    s->view = *ix;
+    pag_index& v = s->view;
+    v.stream = (hipStream_t)stream;
+    v.ws_qrot = nullptr; v.ws_qrot_cap = 0;
+    v.ws_tab = nullptr; v.ws_tab_cap = 0;
+    v.ws_norm = nullptr; v.ws_norm_cap = 0;
+    v.ws_bitmap = nullptr; v.ws_bitmap_cap = 0;
+    v.ws_rings = nullptr; v.ws_rings_cap = 0;
+    v.d_qcounter = nullptr; v.d_counters = nullptr;
+    for (auto& e : v.ev) e = nullptr;
+    v.last_search_ms = v.last_prepare_ms = v.last_build_ms = 0.0;
+    int rc;
+    if ((rc = dev_alloc(&v.d_qcounter, 4)) || (rc = dev_alloc(&v.d_counters, CTR_COUNT))) { searcher_release(s); return rc; }
+    hipError_t e = hipMemsetAsync(v.d_counters, 0, CTR_COUNT * sizeof(u64), v.stream);
+    for (auto& ev : v.ev) if (e == hipSuccess) e = hipEventCreate(&ev);
+    if (e == hipSuccess) e = hipStreamSynchronize(v.stream);
+    if (e != hipSuccess) { searcher_release(s); pag_set_error(std::string("pag_searcher_create: ") + hipGetErrorString(e)); return PAG_EHIP; }
+    *out = s;
+    return PAG_OK;
+}
+
+extern "C" int pag_searcher_search(pag_searcher* s, const float* Q, uint64_t nq, uint32_t K, uint32_t efS,
+                                   int64_t* ids, float* dists) {
+    PAG_CHECK(s != nullptr, PAG_EINVAL, "searcher is null");
+    const pag_index* p = s->parent;
+    // the nodes whose insertion has completed: pag_insert publishes n after its last kernel has finished
+    s->view.n = __atomic_load_n(&p->n, __ATOMIC_ACQUIRE);
+    s->view.n_entry = p->n_entry;
+    s->view.search_b = p->search_b;
+    s->view.flags = p->flags;
+    s->view.seen_log2 = p->seen_log2;
+    return search_impl(&s->view, Q, nq, K, efS, ids, dists);
+}
+
+extern "C" int pag_searcher_get_counters(const pag_searcher* s, pag_counters* out) {
+    PAG_CHECK(s != nullptr, PAG_EINVAL, "searcher is null");
+    return pag_get_counters(&s->view, out);
+}
+
+extern "C" int pag_searcher_free(pag_searcher* s) {
+    if (!s) return PAG_OK;
+    DeviceGuard g(s->view.device);
+    (void)hipStreamSynchronize(s->view.stream);
+    searcher_release(s);
     return PAG_OK;
 }
 

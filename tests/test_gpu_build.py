@@ -137,6 +137,67 @@ def test_online_insertion(orc, cfg1_small):
     assert (ids == oi).mean() >= 0.999
 
 
+def test_search_while_inserting(orc):
+    """A searcher (own workspaces and stream) answers queries while pag_insert grows the index from
+    another host thread (the online setting of Sec. 5.2): every answer is a valid one for the index
+    before or after the insertion, and once the insertion is done the searcher, the index's own
+    pag_search and the oracle agree."""
+    import threading
+    PagIndex = _gpu()
+    w = wl.workload(1, n=40000, nq=200)
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    n0 = 20000
+    bd = torch.from_numpy(base).cuda()
+    qd = torch.from_numpy(q).cuda()
+    gix = PagIndex.build(bd[:n0].contiguous(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                         ef_construction=200, seed=31, capacity=w.n)
+    srch = gix.searcher()
+    gt0, _ = wl.brute_force(base[:n0], q, w.K, w.metric)
+    gt1, _ = wl.brute_force(base, q, w.K, w.metric)
+    i0, d0 = srch.search(qd, w.K, 64)
+    j0, e0 = gix.search(qd, w.K, 64)
+    assert torch.equal(i0, j0) and torch.equal(d0, e0)            # same search, other workspaces
+    torch.cuda.synchronize()
+    extra = bd[n0:].contiguous()
+    err = []
+
+    def grow():
+        try:
+            gix.insert(extra)
+        except Exception as ex:          # pragma: no cover
+            err.append(ex)
+
+    t = threading.Thread(target=grow)
+    t.start()
+    answers = []
+    while t.is_alive() and len(answers) < 2000:
+        ids, dists = srch.search(qd, w.K, 64)
+        answers.append((ids.cpu().numpy(), dists.cpu().numpy()))
+    t.join()
+    assert not err, err
+    assert gix.describe()["n"] == w.n
+    during = sum(1 for ids, _ in answers if ids.max() < n0)
+    assert during >= 1, "no search overlapped with the insertion"
+    print("searches answered while inserting: %d of %d" % (during, len(answers)))
+    q64, b64 = q.astype(np.float64), base.astype(np.float64)
+    for ids, dists in answers[:: max(1, len(answers) // 25)]:
+        assert ids.min() >= 0 and ids.max() < w.n
+        assert np.all(np.diff(dists, axis=1) >= 0)
+        exact = ((q64[:, None, :] - b64[ids]) ** 2).sum(-1)
+        assert np.allclose(dists, exact, rtol=1e-4, atol=1e-5)      # every pair (id, distance) is real
+        assert max(wl.recall_at_k(ids, gt0), wl.recall_at_k(ids, gt1)) >= 0.85
+    # afterwards: searcher == index == oracle on the exported index
+    i1, d1 = srch.search(qd, w.K, 64)
+    j1, e1 = gix.search(qd, w.K, 64)
+    assert torch.equal(i1, j1) and torch.equal(d1, e1)
+    assert wl.recall_at_k(i1.cpu().numpy(), gt1) >= 0.85           # efS = 64 on 40,000 nodes
+    oix = _oracle_view(orc, gix.export())
+    oi, od, _ = oix.search(q, w.K, 64)
+    assert (i1.cpu().numpy() == oi).mean() >= 0.999
+    assert srch.counters()["queries"] >= (len(answers) + 2) * w.nq
+    srch.close()
+
+
 def test_ip_build_clustered(orc):
     PagIndex = _gpu()
     w = wl.workload(3, n=6000, nq=100)
