@@ -66,7 +66,7 @@ def online_insertion(args, w, wl, torch, np, PagIndex):
     base = wl.make(w, "base")
     q = wl.make(w, "query")
     log("generated %s: base %s, queries %s in %.1f s" % (w.name, base.shape, q.shape, time.time() - t0))
-    cap = w.n + rounds * per_round
+    cap = w.n + (rounds + 1) * per_round      # one more batch for the concurrent phase
     all_d = torch.empty((cap, w.d), dtype=torch.float32, device="cuda")
     all_d[:w.n] = torch.from_numpy(base)
     del base
@@ -107,6 +107,37 @@ def online_insertion(args, w, wl, torch, np, PagIndex):
                      "search_qps": round(w.nq / ts, 1), "recall": round(rec, 4)})
         log("round %2d: n = %d, insert %.0f vectors/s, search %.0f QPS at efS %d, recall@%d %.4f" %
             (r + 1, n, per_round / dt, w.nq / ts, efS, w.K, rec))
+    # ---- one more batch, inserted while a searcher answers query batches from this thread ----
+    import threading
+    x = wl.make(w, "insert%d" % rounds, n=per_round)
+    all_d[n:n + per_round] = torch.from_numpy(x)
+    srch = ix.searcher()
+    srch.search(q_d, w.K, efS)
+    torch.cuda.synchronize()
+    timing = {}
+
+    def grow():
+        t = time.perf_counter()
+        ix.insert(all_d[n:n + per_round])
+        timing["insert_s"] = time.perf_counter() - t
+
+    th = threading.Thread(target=grow)
+    t1 = time.perf_counter()
+    th.start()
+    batches = 0
+    while th.is_alive():
+        ids, _ = srch.search(q_d, w.K, efS)
+        batches += 1
+    t_search = time.perf_counter() - t1
+    th.join()
+    gt, _ = wl.brute_force_torch(all_d[:n], q_d, w.K, w.metric)           # the last answer saw n or n + batch nodes
+    rec_c = wl.recall_at_k(ids.cpu().numpy(), gt)
+    concurrent = {"insert_vectors_per_s": round(per_round / timing["insert_s"], 1),
+                  "search_qps_meanwhile": round(batches * w.nq / t_search, 1), "query_batches": batches,
+                  "recall_of_last_batch_vs_index_before": round(rec_c, 4)}
+    log("concurrent: insert %.0f vectors/s while a searcher answered %d batches at %.0f QPS (recall %.4f)" %
+        (per_round / timing["insert_s"], batches, batches * w.nq / t_search, rec_c))
+    srch.close()
     out = {"metric": "online insertion throughput (1 GPU)", "value": round(rounds * per_round / ins_time, 1),
            "unit": "vectors/s", "n_gpus": 1, "steps": rounds, "warmup": 0,
            "ms_per_step": round(1e3 * ins_time / rounds, 3), "higher_is_better": True, "scaling": "weak",
@@ -114,7 +145,8 @@ def online_insertion(args, w, wl, torch, np, PagIndex):
            "config": {"workload": "cfg5 %s: start n=%d d=%d, %d rounds x (insert %d, search %d queries) K=%d deg=%d "
                                   "P=%d efC=%d efS=%d" % (w.name, w.n, w.d, rounds, per_round, w.nq, w.K, w.deg, w.P,
                                                            args.efc, efS),
-                      "initial_build_seconds": round(build_s, 2), "rounds": rows},
+                      "initial_build_seconds": round(build_s, 2), "rounds": rows,
+                      "insert_and_search_at_once": concurrent},
            "roofline": None, "cpu_baseline": None}
     print(json.dumps(out), flush=True)
 
