@@ -547,6 +547,27 @@ int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, 
     if (*lds > 65536) { pag_set_error("search: working set, tables and seen set need more than 64 KB of LDS per wave"); return PAG_EUNSUPPORTED; }
     int rc = pag_search_max_grid(ix, b, *lds, grid);
     if (rc) return rc;
+    // Long searches use the LDS hash only for their first nodes.  Where the registers of the kernel
+    // would allow more waves per CU than this LDS footprint does, a smaller hash buys them.  The
+    // comparison is made with half a KB of slack: a footprint that only just fits the count the
+    // occupancy query reports did not reach it in measurements.
+    if (a->blog && !ix->seen_log2) {
+        const u32 slack = 512;
+        int best = 0;
+        if ((rc = pag_search_max_grid(ix, b, *lds + slack, &best))) return rc;
+        for (u32 lg = a->hlog - 1; lg >= 7; --lg) {
+            SearchArgs t = *a;
+            t.hlog = lg;
+            const u32 l2 = (u32)pag_search_lds_bytes(L, b, lg, t.blog, &t);
+            int g2 = 0;
+            if ((rc = pag_search_max_grid(ix, b, l2 + slack, &g2))) return rc;
+            if (g2 > best) {
+                best = g2;
+                *a = t; *lds = l2;
+                if ((rc = pag_search_max_grid(ix, b, l2, grid))) return rc;
+            }
+        }
+    }
     // per-wave spill bitmaps of the seen set: one bit per node, rounded to 16 bytes
     a->bitmap_words = ((u64)ix->capacity + 127) / 128 * 4;
     const u64 need = (u64)*grid * a->bitmap_words;

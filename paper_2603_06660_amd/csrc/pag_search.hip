@@ -3,38 +3,47 @@
 #include "pag_internal.h"
 
 typedef void (*pag_search_fn)(const SearchArgs);   // selectors: one per (row chunks per lane, code dwords)
-pag_search_fn pag_search_fn_nq1_cw2(int, bool);
-pag_search_fn pag_search_fn_nq1_cw4(int, bool);
-pag_search_fn pag_search_fn_nq1_cw8(int, bool);
-pag_search_fn pag_search_fn_nq2_cw2(int, bool);
-pag_search_fn pag_search_fn_nq2_cw4(int, bool);
-pag_search_fn pag_search_fn_nq2_cw8(int, bool);
-pag_search_fn pag_search_fn_nq3_cw2(int, bool);
-pag_search_fn pag_search_fn_nq3_cw4(int, bool);
-pag_search_fn pag_search_fn_nq3_cw8(int, bool);
-pag_search_fn pag_search_fn_nq4_cw2(int, bool);
-pag_search_fn pag_search_fn_nq4_cw4(int, bool);
-pag_search_fn pag_search_fn_nq4_cw8(int, bool);
-pag_search_fn pag_search_fn_nq6_cw2(int, bool);
-pag_search_fn pag_search_fn_nq6_cw4(int, bool);
-pag_search_fn pag_search_fn_nq6_cw8(int, bool);
-pag_search_fn pag_search_fn_nq8_cw2(int, bool);
-pag_search_fn pag_search_fn_nq8_cw4(int, bool);
-pag_search_fn pag_search_fn_nq8_cw8(int, bool);
-pag_search_fn pag_search_fn_nq12_cw2(int, bool);
-pag_search_fn pag_search_fn_nq12_cw4(int, bool);
-pag_search_fn pag_search_fn_nq12_cw8(int, bool);
+pag_search_fn pag_search_fn_nq1_cw2(int, int);
+pag_search_fn pag_search_fn_nq1_cw4(int, int);
+pag_search_fn pag_search_fn_nq1_cw8(int, int);
+pag_search_fn pag_search_fn_nq2_cw2(int, int);
+pag_search_fn pag_search_fn_nq2_cw4(int, int);
+pag_search_fn pag_search_fn_nq2_cw8(int, int);
+pag_search_fn pag_search_fn_nq3_cw2(int, int);
+pag_search_fn pag_search_fn_nq3_cw4(int, int);
+pag_search_fn pag_search_fn_nq3_cw8(int, int);
+pag_search_fn pag_search_fn_nq4_cw2(int, int);
+pag_search_fn pag_search_fn_nq4_cw4(int, int);
+pag_search_fn pag_search_fn_nq4_cw8(int, int);
+pag_search_fn pag_search_fn_nq6_cw2(int, int);
+pag_search_fn pag_search_fn_nq6_cw4(int, int);
+pag_search_fn pag_search_fn_nq6_cw8(int, int);
+pag_search_fn pag_search_fn_nq8_cw2(int, int);
+pag_search_fn pag_search_fn_nq8_cw4(int, int);
+pag_search_fn pag_search_fn_nq8_cw8(int, int);
+pag_search_fn pag_search_fn_nq12_cw2(int, int);
+pag_search_fn pag_search_fn_nq12_cw4(int, int);
+pag_search_fn pag_search_fn_nq12_cw8(int, int);
 
 static pag_search_fn pick(u32 d, u32 b, bool half, u32 cw) {
     int nw = 1;                                       // entries of W per lane: 64 * nw >= b
     while (64u * nw < b) nw *= 2;
-    const u32 per_chunk_row = half ? 512 : 256;       // elements covered by one 16-byte chunk per lane
+    // how a row is cut into per-lane chunks: fp32 rows in 16-byte chunks (256 elements per chunk
+    // row); 16-bit rows in 16-byte chunks (512 elements) or, when that would leave more of the last
+    // chunk row empty, in 8-byte chunks (256 elements)
+    int vm = 0;
+    u32 per_chunk_row = 256;
+    if (half) {
+        const u32 waste16 = (d + 511) / 512 * 512 - d, waste8 = (d + 255) / 256 * 256 - d;
+        vm = waste8 < waste16 ? 2 : 1;
+        per_chunk_row = vm == 1 ? 512 : 256;
+    }
     const u32 chunks = (d + per_chunk_row - 1) / per_chunk_row;
 #define PAG_PICK_CW(NQ)                                              \
     switch (cw) {                                                    \
-        case 2: return pag_search_fn_nq##NQ##_cw2(nw, half);         \
-        case 4: return pag_search_fn_nq##NQ##_cw4(nw, half);         \
-        case 8: return pag_search_fn_nq##NQ##_cw8(nw, half);         \
+        case 2: return pag_search_fn_nq##NQ##_cw2(nw, vm);         \
+        case 4: return pag_search_fn_nq##NQ##_cw4(nw, vm);         \
+        case 8: return pag_search_fn_nq##NQ##_cw8(nw, vm);         \
         default: return nullptr;                                     \
     }
     if (chunks <= 1) { PAG_PICK_CW(1) }

@@ -25,6 +25,8 @@
 #include "pag_internal.h"
 #include "pag_wave.h"
 
+#include <type_traits>
+
 namespace pagk {
 
 __device__ __forceinline__ u32 rdlane(u32 v, int l) { return (u32)__builtin_amdgcn_readlane((int)v, l); }
@@ -155,11 +157,17 @@ __device__ __forceinline__ float table_sum(u32 t_base, const u32 (&cwv)[CW]) {
     return S;
 }
 
-// NQ: 16-byte chunks of a stored vector per lane; NW: entries of W / R_L per lane; HALF: the store
-// holds 16-bit floats (8 elements per chunk, widened to fp32 on use) instead of fp32 (4 per chunk);
-// CW: dwords of 4-bit codes per neighbour (2, 4 or 8 for up to 16, 32 or 64 subspaces).
-template <int NQ, int NW, bool HALF, int CW>
+// NQ: chunks of a stored vector per lane (a chunk is what one lane loads at once); NW: entries of
+// W / R_L per lane; VM: how the store is read -- 0: fp32, 16-byte chunks of 4 elements; 1: 16-bit
+// floats, 16-byte chunks of 8 elements; 2: 16-bit floats, 8-byte chunks of 4 elements (for row
+// lengths that would leave half of the lanes idle in the last 16-byte chunk); 16-bit values are
+// widened to fp32 on use; CW: dwords of 4-bit codes per neighbour (2, 4 or 8 for up to 16, 32 or
+// 64 subspaces).
+template <int NQ, int NW, int VM, int CW>
 struct Wave {
+    static constexpr bool HALF = VM != 0;
+    static constexpr int EPC = VM == 1 ? 8 : 4;     // elements per chunk
+    using Chunk = std::conditional_t<VM == 2, uint2, uint4>;
     // constant for the kernel
     const SearchArgs A;
     const int lane;
@@ -170,7 +178,7 @@ struct Wave {
     u64 *SA, *SB, *RF, *RT;
     u32* bitmap;
     // per query
-    static constexpr int QV = HALF ? 2 * NQ : NQ;   // float4 registers holding the query
+    static constexpr int QV = NQ * EPC / 4;         // float4 registers holding the query
     static constexpr bool RINGS_IN_HBM = NW > 2;    // matches the host's LDS carve-up
     float4 q[QV];
     u64 W[NW];
@@ -178,7 +186,7 @@ struct Wave {
     u32 nW, nRL;
     u32 cntF, hdF, cntT, hdT;       // rings: valid entries (<= b) and total pushes; slot = push number & ring mask
     u32 n_hash, n_spill;
-    u32 tail_idx;                   // chunk index this lane reads for the last 16-byte chunk of a row (0 if past the end)
+    u32 tail_idx;                   // chunk index this lane reads for the last chunk of a row (0 if past the end)
     u32 tail_mask;                  // all ones if that chunk lies inside the row, else zero
     // adjacency record requested ahead of time for the node that will be expanded next
     u32 nx_id;                      // whose record pf_* holds (PAG_EMPTY: none)
@@ -207,7 +215,7 @@ struct Wave {
             RT = (u64*)(smem + a.off_rt);
         }
         bitmap = a.bitmap + (u64)blockIdx.x * a.bitmap_words;
-        const bool tail_ok = ((NQ - 1) * 64 + (u32)ln) * (HALF ? 8u : 4u) < a.d;
+        const bool tail_ok = ((NQ - 1) * 64 + (u32)ln) * (u32)EPC < a.d;
         tail_idx = tail_ok ? (NQ - 1) * 64 + (u32)ln : 0u;
         tail_mask = tail_ok ? 0xFFFFFFFFu : 0u;
         s_hops = s_tests = s_passes = s_exact = s_rounds = s_rf = s_rt = s_spill = s_queries = 0;
@@ -273,25 +281,27 @@ struct Wave {
     // one rounding to fp32 at the end.  Two buffers of GB vectors each alternate: while one is
     // reduced the other one's loads are in flight.  No load sits inside a branch (a buffer without
     // a passer left simply re-reads the last row), which keeps the wait counts exact.
-    static constexpr int GB = NQ <= 4 ? 2 : 1;
+    static constexpr int GB = NQ * (int)sizeof(Chunk) <= 64 ? 2 : 1;
 
     // Branch-free row load: only the last chunk can run past the row; there the lane re-reads chunk
     // 0 (in bounds) and the value is replaced by zeros, so no load ever sits inside a branch and the
     // loads of several rows stay in flight together.
-    __device__ __forceinline__ void load_vec(uint4 (&v)[NQ], u32 id) const {
-        const uint4* p = (const uint4*)((const char*)A.vec + (u64)id * A.d * (HALF ? 2 : 4));
+    __device__ __forceinline__ void load_vec(Chunk (&v)[NQ], u32 id) const {
+        const Chunk* p = (const Chunk*)((const char*)A.vec + (u64)id * A.d * (HALF ? 2 : 4));
 #pragma unroll
         for (int c = 0; c < NQ - 1; ++c) v[c] = p[c * 64 + lane];
-        const uint4 t = p[tail_idx];
-        v[NQ - 1] = make_uint4(t.x & tail_mask, t.y & tail_mask, t.z & tail_mask, t.w & tail_mask);
+        Chunk t = p[tail_idx];
+        t.x &= tail_mask; t.y &= tail_mask;
+        if constexpr (VM != 2) { t.z &= tail_mask; t.w &= tail_mask; }
+        v[NQ - 1] = t;
     }
 
     // sum over this lane's elements of fl32(q - x)^2, accumulated in fp64
-    __device__ __forceinline__ double lane_partial(const uint4 (&v)[NQ]) const {
+    __device__ __forceinline__ double lane_partial(const Chunk (&v)[NQ]) const {
         double a = 0.0;
 #pragma unroll
         for (int c = 0; c < NQ; ++c) {
-            if constexpr (HALF) {
+            if constexpr (VM == 1) {
                 const float2 x0 = __half22float2(*(const __half2*)&v[c].x), x1 = __half22float2(*(const __half2*)&v[c].y);
                 const float2 x2 = __half22float2(*(const __half2*)&v[c].z), x3 = __half22float2(*(const __half2*)&v[c].w);
                 const float d0 = q[2 * c].x - x0.x, d1 = q[2 * c].y - x0.y, d2 = q[2 * c].z - x1.x, d3 = q[2 * c].w - x1.y;
@@ -301,6 +311,11 @@ struct Wave {
                 a = __builtin_fma((double)d2, (double)d2, a); a = __builtin_fma((double)d3, (double)d3, a);
                 a = __builtin_fma((double)d4, (double)d4, a); a = __builtin_fma((double)d5, (double)d5, a);
                 a = __builtin_fma((double)d6, (double)d6, a); a = __builtin_fma((double)d7, (double)d7, a);
+            } else if constexpr (VM == 2) {
+                const float2 x0 = __half22float2(*(const __half2*)&v[c].x), x1 = __half22float2(*(const __half2*)&v[c].y);
+                const float d0 = q[c].x - x0.x, d1 = q[c].y - x0.y, d2 = q[c].z - x1.x, d3 = q[c].w - x1.y;
+                a = __builtin_fma((double)d0, (double)d0, a); a = __builtin_fma((double)d1, (double)d1, a);
+                a = __builtin_fma((double)d2, (double)d2, a); a = __builtin_fma((double)d3, (double)d3, a);
             } else {
                 const float dx = q[c].x - __uint_as_float(v[c].x), dy = q[c].y - __uint_as_float(v[c].y);
                 const float dz = q[c].z - __uint_as_float(v[c].z), dw = q[c].w - __uint_as_float(v[c].w);
@@ -314,7 +329,7 @@ struct Wave {
     }
 
     // request the rows of the next GB passers (or, when none is left, the last row again)
-    __device__ __forceinline__ void issue(uint4 (&buf)[GB][NQ], int (&pl)[GB], u64& m, int& last, u32 id_lane) const {
+    __device__ __forceinline__ void issue(Chunk (&buf)[GB][NQ], int (&pl)[GB], u64& m, int& last, u32 id_lane) const {
 #pragma unroll
         for (int g = 0; g < GB; ++g) {
             pl[g] = -1;
@@ -323,7 +338,7 @@ struct Wave {
         }
     }
 
-    __device__ __forceinline__ void reduce(const uint4 (&buf)[GB][NQ], const int (&pl)[GB], float& mine) const {
+    __device__ __forceinline__ void reduce(const Chunk (&buf)[GB][NQ], const int (&pl)[GB], float& mine) const {
         double acc[GB];
 #pragma unroll
         for (int g = 0; g < GB; ++g) acc[g] = lane_partial(buf[g]);
@@ -337,7 +352,7 @@ struct Wave {
 
     __device__ __forceinline__ float exact_keys(u32 id_lane, u64 mask) {
         float mine = 0.f;
-        uint4 va[GB][NQ], vb[GB][NQ];
+        Chunk va[GB][NQ], vb[GB][NQ];
         int pa[GB], pb[GB];
         u64 m = mask;
         int last = __ffsll((long long)mask) - 1;
@@ -458,7 +473,7 @@ struct Wave {
 #pragma unroll
             for (int c = 0; c < NQ; ++c) {
                 const u32 idx = c * 64 + lane;
-                if constexpr (HALF) {
+                if constexpr (VM == 1) {
                     const bool in = c < NQ - 1 || idx * 8 < d;
                     q[2 * c] = in ? qp[2 * idx] : make_float4(0.f, 0.f, 0.f, 0.f);
                     q[2 * c + 1] = in ? qp[2 * idx + 1] : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -686,14 +701,14 @@ struct Wave {
 // Persistent waves: every wave pulls query numbers from one counter until the batch is drained,
 // so long and short searches balance themselves; the loop ends for every wave once the counter
 // passes nq.
-template <int NQ, int NW, bool HALF, int CW>
+template <int NQ, int NW, int VM, int CW>
 // Short rows leave room for four waves per SIMD (128 VGPRs, a few dwords of spill); longer rows
 // keep their registers for loads in flight.
-__attribute__((amdgpu_waves_per_eu(NQ <= 3 && NW <= 2 ? 4 : 1, 8)))
+__attribute__((amdgpu_waves_per_eu(VM == 2 && NQ <= 3 && NW <= 2 ? 5 : (NQ <= 3 && NW <= 2 ? 4 : 1), 8)))
 __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
     extern __shared__ __align__(64) unsigned char smem[];   // the table sits first: see table_sum
     const int lane = threadIdx.x;
-    Wave<NQ, NW, HALF, CW> w(A, smem, lane);
+    Wave<NQ, NW, VM, CW> w(A, smem, lane);
     for (;;) {
         u32 qi = 0;
         if (lane == 0) qi = atomicAdd(A.qcounter, 1u);
@@ -707,20 +722,20 @@ __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
 }  // namespace pagk
 
 // One translation unit per (NQ, CW) defines the selector below: the kernels for every number of
-// W / R_L entries per lane (working sets of up to 64, 128, 256, 512, 1024 nodes) and both stores.
+// W / R_L entries per lane (working sets of up to 64, 128, 256, 512, 1024 nodes) and the three ways of reading the store.
 typedef void (*pag_search_fn)(const SearchArgs);
 #define PAG_SEARCH_INSTANCES(NQ, CW)                                                                  \
-    template <bool HALF>                                                                              \
+    template <int VM>                                                                                 \
     static pag_search_fn pag_search_by_nw(int nw) {                                                   \
         switch (nw) {                                                                                 \
-            case 1: return (pag_search_fn)pagk::k_search<NQ, 1, HALF, CW>;                            \
-            case 2: return (pag_search_fn)pagk::k_search<NQ, 2, HALF, CW>;                            \
-            case 4: return (pag_search_fn)pagk::k_search<NQ, 4, HALF, CW>;                            \
-            case 8: return (pag_search_fn)pagk::k_search<NQ, 8, HALF, CW>;                            \
-            case 16: return (pag_search_fn)pagk::k_search<NQ, 16, HALF, CW>;                          \
+            case 1: return (pag_search_fn)pagk::k_search<NQ, 1, VM, CW>;                              \
+            case 2: return (pag_search_fn)pagk::k_search<NQ, 2, VM, CW>;                              \
+            case 4: return (pag_search_fn)pagk::k_search<NQ, 4, VM, CW>;                              \
+            case 8: return (pag_search_fn)pagk::k_search<NQ, 8, VM, CW>;                              \
+            case 16: return (pag_search_fn)pagk::k_search<NQ, 16, VM, CW>;                            \
             default: return nullptr;                                                                  \
         }                                                                                             \
     }                                                                                                 \
-    pag_search_fn pag_search_fn_nq##NQ##_cw##CW(int nw, bool half) {                                  \
-        return half ? pag_search_by_nw<true>(nw) : pag_search_by_nw<false>(nw);                       \
+    pag_search_fn pag_search_fn_nq##NQ##_cw##CW(int nw, int vm) {                                     \
+        return vm == 0 ? pag_search_by_nw<0>(nw) : (vm == 1 ? pag_search_by_nw<1>(nw) : pag_search_by_nw<2>(nw)); \
     }

@@ -1,5 +1,6 @@
-// Instantiations of the search kernel: stored vectors of up to 12 16-byte chunks per lane
-// (fp32 rows of up to 3072 elements, 16-bit rows of up to 6144), 4 code dwords per neighbour.
+// Instantiations of the search kernel: stored vectors of up to 12 chunks per lane (fp32 rows of
+// up to 3072 elements; 16-bit rows of up to 6144 elements in 16-byte chunks or 3072 in 8-byte chunks),
+// 4 code dwords per neighbour (up to 32 subspaces).
 #include "pag_search_kernel.h"
 
 PAG_SEARCH_INSTANCES(12, 4)

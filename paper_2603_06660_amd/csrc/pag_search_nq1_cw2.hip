@@ -1,5 +1,6 @@
-// Instantiations of the search kernel: stored vectors of up to 1 16-byte chunks per lane
-// (fp32 rows of up to 256 elements, 16-bit rows of up to 512), 2 code dwords per neighbour.
+// Instantiations of the search kernel: stored vectors of up to 1 chunks per lane (fp32 rows of
+// up to 256 elements; 16-bit rows of up to 512 elements in 16-byte chunks or 256 in 8-byte chunks),
+// 2 code dwords per neighbour (up to 16 subspaces).
 #include "pag_search_kernel.h"
 
 PAG_SEARCH_INSTANCES(1, 2)

@@ -1,5 +1,6 @@
-// Instantiations of the search kernel: stored vectors of up to 2 16-byte chunks per lane
-// (fp32 rows of up to 512 elements, 16-bit rows of up to 1024), 8 code dwords per neighbour.
+// Instantiations of the search kernel: stored vectors of up to 2 chunks per lane (fp32 rows of
+// up to 512 elements; 16-bit rows of up to 1024 elements in 16-byte chunks or 512 in 8-byte chunks),
+// 8 code dwords per neighbour (up to 64 subspaces).
 #include "pag_search_kernel.h"
 
 PAG_SEARCH_INSTANCES(2, 8)

@@ -1,5 +1,6 @@
-// Instantiations of the search kernel: stored vectors of up to 4 16-byte chunks per lane
-// (fp32 rows of up to 1024 elements, 16-bit rows of up to 2048), 4 code dwords per neighbour.
+// Instantiations of the search kernel: stored vectors of up to 4 chunks per lane (fp32 rows of
+// up to 1024 elements; 16-bit rows of up to 2048 elements in 16-byte chunks or 1024 in 8-byte chunks),
+// 4 code dwords per neighbour (up to 32 subspaces).
 #include "pag_search_kernel.h"
 
 PAG_SEARCH_INSTANCES(4, 4)
