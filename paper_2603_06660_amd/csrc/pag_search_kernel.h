@@ -345,7 +345,8 @@ struct Wave {
         const double tot = fold_sum<GB>(acc);
 #pragma unroll
         for (int g = 0; g < GB; ++g) {
-            const double t = fold_total<GB>(tot, g);
+            const double t = __hiloint2double((int)rdlane((u32)__double2hiint(tot), g * (64 / GB)),
+                                              (int)rdlane((u32)__double2loint(tot), g * (64 / GB)));
             if (lane == pl[g]) mine = (float)t;
         }
     }
