@@ -356,11 +356,6 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
             ix->ws_tab_cap = need;
         }
     }
-    struct FlagGuard {   // indexing always runs with the projection test on
-        pag_index* ix; u32 saved;
-        explicit FlagGuard(pag_index* i) : ix(i), saved(i->flags) { i->flags &= ~PAG_FLAG_NO_PRT; }
-        ~FlagGuard() { ix->flags = saved; }
-    } flag_guard(ix);
     while (pos < n_end) {
         u64 m = std::min<u64>(n_end - pos, max_batch);
         m = std::min<u64>(m, std::max<u64>(1, pos / 2));
@@ -379,6 +374,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         ix->n_entry = (u32)std::min<u64>(pos, 1024);
         if ((rc = pag_search_common(ix, b, ix->efC, pos, &a, &lds, &grid))) return rc;
         a.qrot = qrot; a.tables = ix->ws_tab; a.nq = (u32)m; a.K = b;
+        a.flags &= ~(u32)PAG_FLAG_NO_PRT;          // indexing always runs with the projection test on
         a.cand = ws.cand; a.cand_cnt = ws.cand_cnt; a.cand_cap = cand_cap;
         a.pes = ws.pes;
         if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
