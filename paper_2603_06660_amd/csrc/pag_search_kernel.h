@@ -225,6 +225,19 @@ struct Wave {
 #endif
     }
 
+    // Wave priorities within the SIMD, used with the 16-bit store only: requesting rows comes first (3),
+    // then the screening that leads to the requests (2), then the distance arithmetic (1), and the
+    // bookkeeping of the merge last (0).  With short rows this is worth 9 %; with fp32 rows, where
+    // memory throughput binds, it is not (and costs 1 % on long rows), so there it is left out.
+    __device__ __forceinline__ void set_priority(int p) const {
+        if constexpr (HALF) {
+            if (p == 3) __builtin_amdgcn_s_setprio(3);
+            else if (p == 2) __builtin_amdgcn_s_setprio(2);
+            else if (p == 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
+    }
+
     // lane s < deg reads neighbour slot s of node u: id, a, c and its chunk of 4-bit codes.  The
     // other lanes read slot 0 and get an empty id (their a, c and codes are never used), so the
     // loads sit in straight-line code and can stay in flight across whatever follows.
@@ -330,12 +343,14 @@ struct Wave {
 
     // request the rows of the next GB passers (or, when none is left, the last row again)
     __device__ __forceinline__ void issue(Chunk (&buf)[GB][NQ], int (&pl)[GB], u64& m, int& last, u32 id_lane) const {
+        set_priority(3);
 #pragma unroll
         for (int g = 0; g < GB; ++g) {
             pl[g] = -1;
             if (m) { last = __ffsll((long long)m) - 1; m &= m - 1; pl[g] = last; }
             load_vec(buf[g], rdlane(id_lane, last));
         }
+        set_priority(1);
     }
 
     __device__ __forceinline__ void reduce(const Chunk (&buf)[GB][NQ], const int (&pl)[GB], float& mine) const {
@@ -379,6 +394,7 @@ struct Wave {
     __device__ __forceinline__ void admit(u32 id_lane, u64 mask) {
         const u32 np = (u32)__popcll(mask);
         if (np == 0) {
+            set_priority(0);
             u32 zero[NW];
 #pragma unroll
             for (int s = 0; s < NW; ++s) zero[s] = 0;
@@ -389,6 +405,7 @@ struct Wave {
         const bool pass = (mask >> lane) & 1ull;
         PAG_MARK(2);
         const float dist = exact_keys(id_lane, mask);
+        set_priority(0);
         PAG_MARK(3);
         s_exact += np;
         // seen set
@@ -537,6 +554,7 @@ struct Wave {
                         if (lane == ul) W[s] |= 1ull;
                     }
                 s_hops++;
+                set_priority(2);   // screening leads to the next loads: ahead of other waves' bookkeeping
                 const u32 u = (u32)(ukey & 0xFFFFFFFFull) >> 1;
                 const float Du = __uint_as_float((u32)(ukey >> 32));
                 // threshold ||z_max - q||^2, read once per hop (Eq. 4); +inf while W is not full
