@@ -283,13 +283,17 @@ def main():
     rows_probe = min(8 * w.n, 4_000_000)
     stream_gbs = ix.measure_row_reads(rows_probe, False)
     gather_gbs = ix.measure_row_reads(rows_probe, True)
-    log("row reads on this box: in order %.0f GB/s, scattered %.0f GB/s" % (stream_gbs, gather_gbs))
+    hop_gbs = ix.measure_row_reads(rows_probe, 2)
+    log("row reads on this box: in order %.0f GB/s, scattered %.0f GB/s; with a hop's side traffic %.0f GB/s" %
+        (stream_gbs, gather_gbs, hop_gbs))
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(tag, efS),
                 "kernel": "pagk::k_search", "kernel_ms": round(k_ms, 4), "prepare_ms": round(float(np.mean(prep_ms)), 4),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch),
-                "measured_row_read_GBps": {"in_order": round(stream_gbs, 1), "scattered": round(gather_gbs, 1)},
-                "frac_of_measured_scattered_reads": round(achieved / gather_gbs, 4)}
+                "measured_row_read_GBps": {"in_order": round(stream_gbs, 1), "scattered": round(gather_gbs, 1),
+                                           "scattered_with_hop_side_traffic": round(hop_gbs, 1)},
+                "frac_of_measured_scattered_reads": round(achieved / gather_gbs, 4),
+                "frac_of_measured_hop_traffic": round(achieved / hop_gbs, 4)}
 
     # ---- CPU oracle on the same index, same efS, bounded sample ----
     cpu = None

@@ -193,6 +193,10 @@ int pag_edge_info(const pag_index* ix, uint64_t node_begin, uint64_t node_end, u
  * store, in order (scattered = 0) or in a scattered permutation (scattered = 1), four rows in flight
  * per wavefront, and reports the achieved rate in GB/s.  This is what the exact-distance step of
  * Alg. 2 could reach on this GPU if it did nothing but fetch its vectors.
+ * scattered = 2 reproduces the traffic of whole hops of a long search instead: per seven random rows
+ * one random adjacency record, eight random reads and seven random bit-sets in a per-wave seen-set
+ * bitmap (the index's own workspace, cleared again afterwards); the rate counts rows and records only,
+ * like the algorithmic bytes of the search do.
  */
 int pag_measure_row_reads(const pag_index* ix, uint64_t rows, int scattered, double* gb_per_s);
 

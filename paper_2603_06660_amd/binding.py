@@ -250,9 +250,10 @@ class PagIndex:
         return est
 
     def measure_row_reads(self, rows, scattered):
-        """GB/s at which whole rows of the vector store can be fetched (roofline diagnostic)."""
+        """GB/s at which whole rows of the vector store can be fetched (roofline diagnostic);
+        scattered: 0 in order, 1 scattered, 2 with the side traffic of whole hops (records, seen-set reads and writes)."""
         out = C.c_double(0.0)
-        _check(load_library().pag_measure_row_reads(self._h, C.c_uint64(rows), C.c_int(1 if scattered else 0),
+        _check(load_library().pag_measure_row_reads(self._h, C.c_uint64(rows), C.c_int(int(scattered)),
                                                     C.byref(out)), "pag_measure_row_reads")
         return out.value
 

@@ -783,6 +783,7 @@ extern "C" int pag_measure_row_reads(const pag_index* cix, uint64_t rows, int sc
     pag_index* ix = const_cast<pag_index*>(cix);
     PAG_CHECK(ix && gb_per_s, PAG_EINVAL, "null argument");
     PAG_CHECK(rows >= 1 && ix->n >= 1, PAG_EINVAL, "rows must be >= 1");
+    PAG_CHECK(scattered >= 0 && scattered <= 2, PAG_EINVAL, "mode must be 0, 1 or 2");
     PAG_CHECK(((u64)ix->L.d * (ix->vec_half ? 2 : 4)) % 16 == 0, PAG_EUNSUPPORTED, "rows must be a multiple of 16 bytes");
     DeviceGuard g(ix->device);
     // a multiplier coprime with n makes (counter * stride) mod n a permutation of the rows
@@ -794,6 +795,29 @@ extern "C" int pag_measure_row_reads(const pag_index* cix, uint64_t rows, int sc
     }
     const int grid = ix->num_cu * 16;
     int rc;
+    if (scattered == 2) {
+        // the traffic of whole hops: rows / 7 hops of 7 rows, one record, 8 bitmap reads, 7 bitmap writes each
+        const u64 words = ((u64)ix->capacity + 127) / 128 * 4;
+        const u64 need = (u64)grid * words;
+        if (ix->ws_bitmap_cap < need) {
+            if ((rc = ensure_ws(&ix->ws_bitmap, &ix->ws_bitmap_cap, need))) return rc;
+            PAG_HIP(hipMemsetAsync(ix->ws_bitmap, 0, need * 4, ix->stream));
+        }
+        const u64 hops = std::max<u64>(1, rows / 7);
+        for (int rep = 0; rep < 2; ++rep) {
+            PAG_HIP(hipEventRecord(ix->ev[0], ix->stream));
+            if ((rc = pag_launch_hop_traffic(ix->stream, ix, hops, ix->ws_bitmap, words, ix->d_qcounter + 1, grid))) return rc;
+            PAG_HIP(hipEventRecord(ix->ev[1], ix->stream));
+            PAG_HIP(hipStreamSynchronize(ix->stream));
+        }
+        // searches expect clean bitmaps
+        PAG_HIP(hipMemsetAsync(ix->ws_bitmap, 0, need * 4, ix->stream));
+        PAG_HIP(hipStreamSynchronize(ix->stream));
+        float ms2 = 0.f;
+        PAG_HIP(hipEventElapsedTime(&ms2, ix->ev[0], ix->ev[1]));
+        *gb_per_s = (double)hops * (7.0 * ix->L.d * (ix->vec_half ? 2 : 4) + ix->L.rec_bytes) / ((double)ms2 * 1e6);
+        return PAG_OK;
+    }
     for (int rep = 0; rep < 2; ++rep) {      // first pass warms up, second is timed
         PAG_HIP(hipEventRecord(ix->ev[0], ix->stream));
         if ((rc = pag_launch_row_reads(ix->stream, ix, rows, stride, ix->d_qcounter + 1, grid))) return rc;

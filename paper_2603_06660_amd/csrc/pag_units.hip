@@ -174,6 +174,42 @@ __global__ void __launch_bounds__(64) k_row_reads(const uint4* __restrict__ vec,
     if (acc == 0x9E3779B9u) sink[0] = acc;     // practically never: keeps the loads alive
 }
 
+__device__ __forceinline__ u64 mix64(u64 x) {
+    x ^= x >> 33; x *= 0xff51afd7ed558ccdull; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ull; x ^= x >> 33;
+    return x;
+}
+
+// Diagnostic: the memory traffic of one hop of a long search without any of its arithmetic.  Per
+// "hop": one adjacency record, seven random rows of the vector store (four, then three in flight),
+// eight random words of the wave's seen-set bitmap read and seven random bits of it set -- the mix
+// the search kernel produces at about seven admitted neighbours per hop.  No step of the method.
+__global__ void __launch_bounds__(64) k_hop_traffic(const uint4* __restrict__ vec, u64 row_chunks, const uint4* __restrict__ rec,
+                                                    u64 rec_chunks, u64 n, u64 hops, u32* __restrict__ bitmap,
+                                                    u64 bitmap_words, u32* __restrict__ sink) {
+    const int lane = threadIdx.x;
+    u32 acc = 0;
+    u32* bm = bitmap + (u64)blockIdx.x * bitmap_words;
+    for (u64 h = blockIdx.x; h < hops; h += gridDim.x) {
+        const u64 u = mix64(h * 2654435761ull) % n;
+        for (u64 c = lane; c < rec_chunks; c += 64) { const uint4 t = rec[u * rec_chunks + c]; acc ^= t.x ^ t.y ^ t.z ^ t.w; }
+        if (lane < 8) acc ^= __hip_atomic_load(&bm[mix64(h * 977 + lane) % bitmap_words], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        u64 row[7];
+#pragma unroll
+        for (int g = 0; g < 7; ++g) row[g] = mix64(h * 7 + g + 12345) % n;
+        for (int g0 = 0; g0 < 7; g0 += 4) {
+            for (u64 c = lane; c < row_chunks; c += 64) {
+                uint4 v[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) v[g] = vec[row[g0 + g < 7 ? g0 + g : 6] * row_chunks + c];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) acc ^= v[g].x ^ v[g].y ^ v[g].z ^ v[g].w;
+            }
+        }
+        if (lane < 7) atomicOr(&bm[mix64(h * 31 + lane + 99) % bitmap_words], 1u << (lane & 31));
+    }
+    if (acc == 0x9E3779B9u) sink[0] = acc;
+}
+
 u32 edge_info_lds(const pag_layout& L) { return 2 * L.d * 4 + 2 * L.P * 8 + L.Ppad * 4; }
 
 }  // namespace
@@ -219,6 +255,14 @@ int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edg
     if (n_edges == 0) return PAG_OK;
     hipLaunchKernelGGL(k_edge_info, dim3((unsigned)n_edges), dim3(64), edge_info_lds(ix->L), s, pag_vecs_of(ix), ix->rec,
                        ix->e2, ix->L, ix->cb, edge_list, n_edges, 0ull, 0ull);
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
+}
+
+int pag_launch_hop_traffic(hipStream_t s, const pag_index* ix, u64 hops, u32* bitmap, u64 bitmap_words, u32* sink, int grid) {
+    const u64 row_chunks = (u64)ix->L.d * (ix->vec_half ? 2 : 4) / 16;
+    hipLaunchKernelGGL(k_hop_traffic, dim3((unsigned)grid), dim3(64), 0, s, (const uint4*)ix->vec, row_chunks,
+                       (const uint4*)ix->rec, (u64)ix->L.rec_bytes / 16, ix->n, hops, bitmap, bitmap_words, sink);
     PAG_HIP(hipGetLastError());
     return PAG_OK;
 }
