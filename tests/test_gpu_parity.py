@@ -234,3 +234,16 @@ def test_cosine_and_ip(orc):
     oixc = orc.OracleIndex(oix.vec, oix.adj, oix.a, oix.c, oix.e2, oix.codes, oix.rot, oix.cb, oix.entry, metric=wl.COS)
     gixc = _import(PagIndex, oixc)
     _assert_search_parity(gixc, oixc, (2.5 * q).astype(np.float32), 10, 64, gt)
+
+
+def test_traffic_diagnostics_leave_the_index_usable(orc, cfg1_small, cfg1_oracle_index, imported):
+    """The roofline diagnostics (row reads in order / scattered, whole-hop traffic with seen-set writes) return
+    rates and leave the per-wave seen-set workspaces clean: searches afterwards still match the oracle."""
+    w, base, q, gt, gtk = cfg1_small
+    for mode in (0, 1, 2):
+        assert imported.measure_row_reads(20000, mode) > 0.0
+    imported.set_seen_capacity_log2(6)           # force the bitmap level so that leftovers would show
+    try:
+        _assert_search_parity(imported, cfg1_oracle_index, q, w.K, 64, gt)
+    finally:
+        imported.set_seen_capacity_log2(0)
