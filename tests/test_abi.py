@@ -61,6 +61,10 @@ def test_argument_errors_need_no_gpu(lib):
     h = C.c_void_p()
     assert lib.pag_build(None, C.c_uint64(0), C.c_uint32(8), None, C.byref(h)) == -1      # params null
     assert lib.pag_free(None) == 0
+    s = C.c_void_p()
+    assert lib.pag_searcher_create(None, None, C.byref(s)) == -1 and not s.value
+    assert lib.pag_searcher_search(None, None, C.c_uint64(1), C.c_uint32(1), C.c_uint32(1), None, None) == -1
+    assert lib.pag_searcher_free(None) == 0
 
 
 def test_missing_library_is_an_error(monkeypatch):
