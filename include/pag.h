@@ -111,7 +111,7 @@ typedef struct {
     uint64_t rounds;             /* TFB rounds */
     uint64_t rf_overflow;        /* entries overwritten in the ring R_F */
     uint64_t rt_overflow;        /* entries overwritten in the ring R_T */
-    uint64_t seen_spills;        /* seen-set insertions that went to the HBM bitmap instead of LDS */
+    uint64_t seen_spills;        /* seen-set insertions that went to the HBM bitmap (all of them in long searches) */
     double   last_search_kernel_ms; /* HIP-event time of the search kernel of the last pag_search */
     double   last_prepare_ms;       /* HIP-event time of rotation + projection tables of the last pag_search */
     double   last_build_ms;         /* wall time of the last pag_build / pag_insert */
@@ -160,7 +160,7 @@ int pag_get_counters(const pag_index* ix, pag_counters* out);
 int pag_reset_counters(pag_index* ix);
 /* Changes search-time settings of an existing index: working-set size (0 = max(10,K)) and PAG_FLAG_* bits. */
 int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t flags);
-/* log2 of the per-query LDS seen-set capacity; 0 = choose from efS.  Small values exercise the HBM spill path. */
+/* log2 of the slots of the per-query LDS seen-set table; 0 = choose from efS.  Small values exercise the HBM spill path. */
 int pag_set_seen_capacity_log2(pag_index* ix, uint32_t log2_slots);
 
 /*

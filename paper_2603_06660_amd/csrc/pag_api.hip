@@ -514,10 +514,10 @@ static int prepare(pag_index* ix, const float* Q, u64 nq, float* qrot, float* ta
     return pag_launch_tables(ix->stream, qrot, nq, ix->L, ix->cb, tables);
 }
 
-// Seen-set sizing.  First level: an exact LDS hash.  A search expected to compute at most ~1000
-// exact distances (entries + a few per visited node) gets a hash that holds all of them.  Longer
-// searches get a small hash for the early nodes, and behind it the per-wave HBM bitmap guarded by
-// a 4 KB LDS Bloom filter: large LDS tables cost more in occupancy than the bitmap costs in loads.
+// Seen-set sizing.  A search expected to compute at most ~1000 exact distances (entries + a few per
+// visited node) gets an exact LDS hash that holds all of them.  Longer searches keep every id in the
+// per-wave HBM bitmap, guarded by a 4 KB LDS Bloom filter, and use a small LDS table as a cache of
+// recently admitted ids: large LDS tables cost more in occupancy than the bitmap costs in loads.
 static void seen_sizes_for(const pag_index* ix, u32 ef, u32 b, u32* hlog, u32* blog) {
     const u32 expected = b + 8 * std::max(ef, b);
     if (expected <= 1024) {

@@ -6,8 +6,10 @@
 //   W            registers, sorted ascending by key; rank r lives in slot r/64 of lane r%64 (NW slots, b <= 64 NW)
 //   R_L          registers, same placement (capacity K <= b)
 //   table T      LDS, float [Ppad][16]
-//   seen set     LDS open-addressing hash of node ids (exact); overflows into a per-wave HBM bitmap
-//                that an LDS Bloom filter guards
+//   seen set     short searches: LDS open-addressing hash of node ids (exact; overflows into a
+//                per-wave HBM bitmap).  Long searches: every id goes to the per-wave HBM bitmap,
+//                an LDS Bloom filter says which lookups can skip it, and the LDS table is a
+//                direct-mapped cache of recently admitted ids (most re-encounters are recent)
 //   R_F, R_T     rings (power-of-two buffers, the last b pushes are valid): LDS, or per-wave HBM
 //                buffers for working sets above 128 nodes, which are pushed to rarely and read
 //                once per round
@@ -409,8 +411,11 @@ struct Wave {
         PAG_MARK(3);
         s_exact += np;
         // seen set
-        const bool spill = (n_hash + np) > (1u << (A.hlog - 1));
+        // long searches (Bloom regime): every node goes to the bitmap, and the LDS table is a direct-mapped
+        // cache of recently admitted ids (a hit is definite); short searches: exact open-addressing hash
+        const bool spill = A.blog != 0 || (n_hash + np) > (1u << (A.hlog - 1));
         if (pass) {
+            if (A.blog != 0) H[hash_slot(id_lane, A.hlog)] = id_lane;
             if (!spill) hash_insert(H, A.hlog, id_lane);
             else {
                 atomicOr(&bitmap[id_lane >> 5], 1u << (id_lane & 31));
@@ -584,7 +589,7 @@ struct Wave {
                 // the Bloom filter) the bitmap word, requested now and consumed only after the table
                 // sums so that its latency overlaps with them
                 bool cand = in_graph;
-                if (cand) cand = !hash_contains(H, A.hlog, id);
+                if (cand) cand = A.blog != 0 ? H[hash_slot(id, A.hlog)] != id : !hash_contains(H, A.hlog, id);
                 u32 bm_word = 0;
                 if (n_spill && cand && (A.blog == 0 || bloom_maybe(BL, A.blog, id)))
                     bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
