@@ -317,10 +317,12 @@ def main():
         t2 = time.perf_counter()
         oix.search(q[:n1], w.K, efS, threads=1)
         dt1 = time.perf_counter() - t2
+        oracle_skipped = round(1.0 - oc["passes"] / max(1, oc["tests"]), 4)
         cpu = {"value": round(sample / dt, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
                "sample": "first %d of %d queries, same exported index, efS=%d; id-slot agreement with the GPU %.5f"
                          % (sample, w.nq, efS, agree),
-               "single_thread": {"value": round(n1 / dt1, 1), "unit": "queries/s", "sample": "first %d queries" % n1}}
+               "single_thread": {"value": round(n1 / dt1, 1), "unit": "queries/s", "sample": "first %d queries" % n1},
+               "skipped_fraction_of_unseen_neighbours": oracle_skipped}
         log("cpu oracle: %.1f QPS on %d threads over %d queries; GPU/oracle id agreement %.5f" %
             (sample / dt, cores, sample, agree))
 

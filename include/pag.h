@@ -105,7 +105,9 @@ typedef struct {
     uint32_t adj_record_bytes;   /* size of one node's adjacency record in HBM */
     uint64_t queries;
     uint64_t hops;               /* expanded nodes (n' of Sec. 4.2) */
-    uint64_t tests;              /* neighbours submitted to the projection test */
+    uint64_t tests;              /* neighbours the projection test was evaluated for: the unseen ones; in long
+                                    searches also already-seen ones that only the second level of the seen
+                                    set would have recognised (it is consulted for passing neighbours only) */
     uint64_t passes;             /* of those, how many passed (gamma = passes / tests) */
     uint64_t exact;              /* exact distances computed, entry nodes included */
     uint64_t rounds;             /* TFB rounds */

@@ -585,13 +585,14 @@ struct Wave {
                 nx_id = PAG_EMPTY;
                 PAG_MARK(1);
                 const bool in_graph = id != PAG_EMPTY && id < A.n_limit;
-                // seen-set lookup: LDS hash, then (for ids that may live in the HBM bitmap according to
-                // the Bloom filter) the bitmap word, requested now and consumed only after the table
-                // sums so that its latency overlaps with them
+                // seen-set lookup.  Short searches: the exact LDS hash, then the bitmap word if the hash has
+                // overflowed, requested now and consumed after the table sums.  Long searches: the LDS cache of
+                // recent ids now; the Bloom filter and the bitmap only for the neighbours that pass the test
+                // (a bitmap read costs more than the table sums of the seen neighbours it would spare).
                 bool cand = in_graph;
                 if (cand) cand = A.blog != 0 ? H[hash_slot(id, A.hlog)] != id : !hash_contains(H, A.hlog, id);
                 u32 bm_word = 0;
-                if (n_spill && cand && (A.blog == 0 || bloom_maybe(BL, A.blog, id)))
+                if (A.blog == 0 && n_spill && cand)
                     bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 // projection test: S = sum_l T[l][code_l] (increasing l), est = D_u + c - 2 a S
                 float est = 0.f;
@@ -603,9 +604,15 @@ struct Wave {
                     }
                     est = __builtin_fmaf(-2.0f * ea, S, Du + ec);
                 }
-                cand = cand && !((bm_word >> (id & 31)) & 1u);
-                bool pass = cand;
-                if (!(A.flags & PAG_FLAG_NO_PRT)) pass = cand && (est < Dmax);
+                if (A.blog != 0) {
+                    // long searches: only neighbours that pass the test are looked up in the Bloom filter and the bitmap
+                    const bool maybe = cand && ((A.flags & PAG_FLAG_NO_PRT) || est < Dmax) && bloom_maybe(BL, A.blog, id);
+                    if (maybe) bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                const bool unseen = cand && !((bm_word >> (id & 31)) & 1u);
+                bool pass = unseen;
+                if (!(A.flags & PAG_FLAG_NO_PRT)) pass = unseen && (est < Dmax);
+                if (A.blog == 0) cand = unseen;
                 if (want_pes) {
                     // PES screening (Eq. 5): max_i (cos theta_i / cos beta_i - delta_i) < 0 for all neighbours
                     // <=> every estimate est_i exceeds D_u, i.e. no neighbour of u looks closer to v than
