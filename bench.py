@@ -336,7 +336,7 @@ def main():
                    "efS": efS, "efS_within_configured_grid": bool(efS <= max(w.efs_grid)),
                    "recall_at_K": round(recall, 4), "recall_target_reached": reached,
                    "qps_interpolated_at_recall_%.2f" % TARGET_RECALL: interp,
-                   "skipped_fraction": round(1.0 - c["passes"] / max(1, c["tests"]), 4),
+                   "skipped_fraction_of_evaluated_neighbours": round(1.0 - c["passes"] / max(1, c["tests"]), 4),
                    "hops_per_query": round(c["hops"] / max(1, c["queries"]), 1),
                    "exact_per_query": round(c["exact"] / max(1, c["queries"]), 1),
                    "build_seconds": round(build_s, 2), "sweep": curve},
