@@ -411,18 +411,24 @@ struct Wave {
         PAG_MARK(3);
         s_exact += np;
         // seen set
-        // long searches (Bloom regime): every node goes to the bitmap, and the LDS table is a direct-mapped
-        // cache of recently admitted ids (a hit is definite); short searches: exact open-addressing hash
-        const bool spill = A.blog != 0 || (n_hash + np) > (1u << (A.hlog - 1));
-        if (pass) {
-            if (A.blog != 0) H[hash_slot(id_lane, A.hlog)] = id_lane;
-            if (!spill) hash_insert(H, A.hlog, id_lane);
-            else {
+        if (A.blog != 0) {
+            // long searches: every node goes to the bitmap and the Bloom filter; the LDS table keeps the
+            // most recently admitted id per slot (a hit there is definite)
+            if (pass) {
+                H[hash_slot(id_lane, A.hlog)] = id_lane;
                 atomicOr(&bitmap[id_lane >> 5], 1u << (id_lane & 31));
-                if (A.blog) bloom_set(BL, A.blog, id_lane);
+                bloom_set(BL, A.blog, id_lane);
             }
+            n_spill += np; s_spill += np;
+        } else {
+            // short searches: exact open-addressing hash, kept at most half full; beyond that the bitmap
+            const bool spill = (n_hash + np) > (1u << (A.hlog - 1));
+            if (pass) {
+                if (!spill) hash_insert(H, A.hlog, id_lane);
+                else atomicOr(&bitmap[id_lane >> 5], 1u << (id_lane & 31));
+            }
+            if (spill) { n_spill += np; s_spill += np; } else n_hash += np;
         }
-        if (spill) { n_spill += np; s_spill += np; } else n_hash += np;
 
         const u64 pk = pass ? (((u64)__float_as_uint(dist) << 32) | ((u64)id_lane << 1)) : PAG_KEY_INVALID;
         u32 cntW[NW];
