@@ -115,28 +115,30 @@ __global__ void __launch_bounds__(64) k_edge_info(pag_vecs V, uint8_t* __restric
     for (u32 l = L.P + lane; l < L.Ppad; l += 64) code[l] = 0u;
     const double e2 = wave_sum(e2p);
     __syncthreads();
-    // lps lanes share a subspace, each scanning 16 / lps of its reference vectors; the group's
-    // argmax keeps the smallest index among equal values, as a scan in index order would
-    const u32 lps = L.P <= 16 ? 4u : (L.P <= 32 ? 2u : 1u);
-    const u32 part = (u32)lane % lps, per_part = PAG_NCODE / lps;
-    for (u32 l = (u32)lane / lps; l < L.P; l += 64 / lps) {
-        double bv = 0.0;
-        u32 bj = 0;
-        for (u32 j = part * per_part; j < (part + 1) * per_part; ++j) {
-            const float* r = cb + ((u64)l * PAG_NCODE + j) * L.dsub;
-            double acc = 0.0;
-            for (u32 k = 0; k < L.dsub; ++k) acc = __builtin_fma((double)r[k], (double)diff[l * L.dsub + k], acc);
-            if (j == part * per_part || acc > bv) { bv = acc; bj = j; }
-        }
-        for (u32 o = 1; o < lps; o <<= 1) {
-            const double ov = __shfl_xor(bv, (int)o, 64);
-            const u32 oj = (u32)__shfl_xor((int)bj, (int)o, 64);
+    // Four subspaces at a time: each 16-lane row takes one subspace, each of its lanes one of the
+    // sixteen reference vectors, so that a row reads one contiguous 16 x dsub block of the codebook.
+    // The dot products run over k in order; the row's argmax keeps the smallest index among equal
+    // values, as a scan in index order would.
+    const u32 j = (u32)lane & 15u, row = (u32)lane >> 4;
+    for (u32 l0 = 0; l0 < L.P; l0 += 4) {
+        const u32 l = l0 + row;
+        const bool live = l < L.P;
+        const u32 lc = live ? l : 0u;
+        const float* r = cb + ((u64)lc * PAG_NCODE + j) * L.dsub;
+        double acc = 0.0;
+        for (u32 k = 0; k < L.dsub; ++k) acc = __builtin_fma((double)r[k], (double)diff[lc * L.dsub + k], acc);
+        double bv = acc;
+        u32 bj = j;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+            const double ov = __shfl_xor(bv, o, 64);
+            const u32 oj = (u32)__shfl_xor((int)bj, o, 64);
             if (ov > bv || (ov == bv && oj < bj)) { bv = ov; bj = oj; }
         }
-        if (part == 0) {
-            const float* r = cb + ((u64)l * PAG_NCODE + bj) * L.dsub;
+        if (live && j == 0) {
+            const float* rb = cb + ((u64)l * PAG_NCODE + bj) * L.dsub;
             double o = 0.0;
-            for (u32 k = 0; k < L.dsub; ++k) o = __builtin_fma((double)r[k], (double)uu[l * L.dsub + k], o);
+            for (u32 k = 0; k < L.dsub; ++k) o = __builtin_fma((double)rb[k], (double)uu[l * L.dsub + k], o);
             best[l] = bv; offs[l] = o; code[l] = bj;
         }
     }
