@@ -95,14 +95,24 @@ __global__ void __launch_bounds__(64) k_init_clique(pag_vecs vec, uint8_t* __res
     if ((u32)lane < L.deg) ids[lane] = (u32)lane < take ? (u32)(sorted[lane] & 0xFFFFFFFFull) : PAG_EMPTY;
 }
 
+// segment bounds of the per-node candidate lists for the segmented sort
+__global__ void k_cand_segments(const u32* __restrict__ cand_cnt, u32 m, u32 cand_cap, int* __restrict__ seg_begin,
+                                int* __restrict__ seg_end) {
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= m) return;
+    const u32 c = cand_cnt[i] < cand_cap ? cand_cnt[i] : cand_cap;
+    seg_begin[i] = (int)(i * cand_cap);
+    seg_end[i] = (int)(i * cand_cap + c);
+}
+
 // ---- RobustPrune over R_L of each new node (Eq. 1, alpha = 1) ----
-// cand: per node the keys collected by the search (dist bits << 32 | id << 1 | visited), unsorted
-// across rounds.  Sorted ascending, cut to efC, then scanned: a candidate is kept unless an
+// cand_sorted: per node the keys collected by the search (dist bits << 32 | id << 1 | visited),
+// sorted ascending by a segmented radix sort over bits 1..63.  Cut to efC, then scanned: a candidate is kept unless an
 // already kept s has ||s - c|| <= ||v - c||.  Writes N_out(v) into v's record and one reverse
 // pair per kept neighbour: key = target << 32 | dist bits, value = v.
 __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restrict__ recs,
-                                                  pag_layout L, u32 node0, u32 m, const u64* __restrict__ cand,
-                                                  u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
+                                                  pag_layout L, u32 node0, u32 m,
+                                                  const u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
                                                   const u64* __restrict__ pes,
                                                   u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -111,21 +121,12 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
     const u32 vi = blockIdx.x;
     if (vi >= m) return;
     // the sorted list lives in HBM: it is read once, front to back, and keeping it out of LDS lets
-    // four times as many waves hide each other's row-fetch latency
-    u64* sorted = cand_sorted + (u64)vi * cand_cap;
+    // many waves hide each other's row-fetch latency
+    const u64* sorted = cand_sorted + (u64)vi * cand_cap;   // ascending by (dist, id); bit 0 is the visited flag
     const int lane = threadIdx.x;
     const u32 v = node0 + vi;
-    const u64* mine = cand + (u64)vi * cand_cap;
     u32 nc = cand_cnt[vi];
     if (nc > cand_cap) nc = cand_cap;
-    for (u32 i = lane; i < nc; i += 64) {
-        const u64 k = mine[i] & ~1ull;           // drop the visited flag
-        u32 r = 0;
-        for (u32 j = 0; j < nc; ++j) r += ((mine[j] & ~1ull) < k) ? 1u : 0u;
-        sorted[r] = k;
-    }
-    __threadfence();           // entries written by other lanes of this wave are read below
-    __syncthreads();
     if (nc > efC) nc = efC;
     u32 nk = 0;
     u32 my_id = PAG_EMPTY;       // lane s holds kept[s]
@@ -284,8 +285,10 @@ struct BuildWs {
     u64 *rk_in = nullptr, *rk_out = nullptr; u32 *rv_in = nullptr, *rv_out = nullptr;
     u32* edges = nullptr; u32* n_edges = nullptr;
     void* sort_tmp = nullptr; size_t sort_bytes = 0;
+    int *seg_begin = nullptr, *seg_end = nullptr;
+    void* seg_tmp = nullptr; size_t seg_bytes = 0;
     ~BuildWs() {
-        void* p[] = { cand, cand_sorted, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, sort_tmp };
+        void* p[] = { cand, cand_sorted, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, sort_tmp, seg_begin, seg_end, seg_tmp };
         for (void* x : p) if (x) (void)hipFree(x);
     }
 };
@@ -341,6 +344,12 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     PAG_HIP(hipcub::DeviceRadixSort::SortPairs(nullptr, ws.sort_bytes, ws.rk_in, ws.rk_out, ws.rv_in, ws.rv_out,
                                                (int)max_pairs, 0, 64, s));
     PAG_ALLOC(ws.sort_tmp, ws.sort_bytes);
+    PAG_ALLOC(ws.seg_begin, max_batch * 4);
+    PAG_ALLOC(ws.seg_end, max_batch * 4);
+    if (max_batch * cand_cap > 0x7FFFFFFFull) { pag_set_error("build: batch x ef_construction exceeds 2^31 candidate slots"); return PAG_EUNSUPPORTED; }
+    PAG_HIP(hipcub::DeviceSegmentedRadixSort::SortKeys(nullptr, ws.seg_bytes, ws.cand, ws.cand_sorted, (int)(max_batch * cand_cap),
+                                                       (int)max_batch, ws.seg_begin, ws.seg_end, 1, 64, s));
+    PAG_ALLOC(ws.seg_tmp, ws.seg_bytes);
     if (ix->vec_half && ix->ws_qrot_cap < max_batch * L.d) {
         if (ix->ws_qrot) (void)hipFree(ix->ws_qrot);
         ix->ws_qrot = nullptr; ix->ws_qrot_cap = 0;
@@ -379,11 +388,17 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         a.pes = ws.pes;
         if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
         if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
-        // 3. RobustPrune -> N_out(v), reverse pairs
+        // 3. candidates of every new node sorted by (dist, id): bits 1..63 of the keys, the visited flag aside
+        hipLaunchKernelGGL(k_cand_segments, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, ws.cand_cnt, (u32)m, cand_cap,
+                           ws.seg_begin, ws.seg_end);
+        PAG_HIP(hipGetLastError());
+        PAG_HIP(hipcub::DeviceSegmentedRadixSort::SortKeys(ws.seg_tmp, ws.seg_bytes, ws.cand, ws.cand_sorted, (int)(m * cand_cap), (int)m,
+                                                           ws.seg_begin, ws.seg_end, 1, 64, s));
+        //    RobustPrune -> N_out(v), reverse pairs
         {
             const u32 plds = L.d * 4 + L.deg * 4;
             hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, (u32)pos, (u32)m,
-                               ws.cand, ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
+                               ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
             PAG_HIP(hipGetLastError());
         }
         // 4. group reverse pairs by target
