@@ -21,6 +21,9 @@ pag_search_fn pag_search_fn_nq6_cw8(int, int);
 pag_search_fn pag_search_fn_nq8_cw2(int, int);
 pag_search_fn pag_search_fn_nq8_cw4(int, int);
 pag_search_fn pag_search_fn_nq8_cw8(int, int);
+pag_search_fn pag_search_fn_nq10_cw2(int, int);
+pag_search_fn pag_search_fn_nq10_cw4(int, int);
+pag_search_fn pag_search_fn_nq10_cw8(int, int);
 pag_search_fn pag_search_fn_nq12_cw2(int, int);
 pag_search_fn pag_search_fn_nq12_cw4(int, int);
 pag_search_fn pag_search_fn_nq12_cw8(int, int);
@@ -38,6 +41,8 @@ static pag_search_fn pick(u32 d, u32 b, bool half, u32 cw) {
         vm = waste8 < waste16 ? 2 : 1;
         per_chunk_row = vm == 1 ? 512 : 256;
     }
+    // chunk rows a stored row needs; the kernel for `chunks` rows or, where that count is not instantiated,
+    // for one more (it masks its last two chunk rows): 1, 2, 3, 4, 6, 8, 10, 12
     const u32 chunks = (d + per_chunk_row - 1) / per_chunk_row;
 #define PAG_PICK_CW(NQ)                                              \
     switch (cw) {                                                    \
@@ -52,6 +57,7 @@ static pag_search_fn pick(u32 d, u32 b, bool half, u32 cw) {
     if (chunks <= 4) { PAG_PICK_CW(4) }
     if (chunks <= 6) { PAG_PICK_CW(6) }
     if (chunks <= 8) { PAG_PICK_CW(8) }
+    if (chunks <= 10) { PAG_PICK_CW(10) }
     if (chunks <= 12) { PAG_PICK_CW(12) }
 #undef PAG_PICK_CW
     return nullptr;

@@ -188,8 +188,12 @@ struct Wave {
     u32 nW, nRL;
     u32 cntF, hdF, cntT, hdT;       // rings: valid entries (<= b) and total pushes; slot = push number & ring mask
     u32 n_hash, n_spill;
-    u32 tail_idx;                   // chunk index this lane reads for the last chunk of a row (0 if past the end)
-    u32 tail_mask;                  // all ones if that chunk lies inside the row, else zero
+    // The last TAILS chunk rows of the NQ may lie partly or wholly beyond the end of a row (the host
+    // picks NQ = the rows needed, or one more where that count is not instantiated): per such chunk the
+    // index this lane reads (0 if past the end) and a mask (all ones if inside the row, else zero)
+    static constexpr int TAILS = NQ >= 5 ? 2 : 1;
+    u32 tail_idx[TAILS];
+    u32 tail_mask[TAILS];
     // adjacency record requested ahead of time for the node that will be expanded next
     u32 nx_id;                      // whose record pf_* holds (PAG_EMPTY: none)
     u32 pf_id, pf_cw[CW];
@@ -217,9 +221,13 @@ struct Wave {
             RT = (u64*)(smem + a.off_rt);
         }
         bitmap = a.bitmap + (u64)blockIdx.x * a.bitmap_words;
-        const bool tail_ok = ((NQ - 1) * 64 + (u32)ln) * (u32)EPC < a.d;
-        tail_idx = tail_ok ? (NQ - 1) * 64 + (u32)ln : 0u;
-        tail_mask = tail_ok ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+        for (int t = 0; t < TAILS; ++t) {
+            const u32 idx = (u32)(NQ - TAILS + t) * 64 + (u32)ln;
+            const bool tail_ok = idx * (u32)EPC < a.d;
+            tail_idx[t] = tail_ok ? idx : 0u;
+            tail_mask[t] = tail_ok ? 0xFFFFFFFFu : 0u;
+        }
         s_hops = s_tests = s_passes = s_exact = s_rounds = s_rf = s_rt = s_spill = s_queries = 0;
 #ifdef PAG_PHASE_TIMERS
         for (int i = 0; i < 6; ++i) s_phase[i] = 0;
@@ -298,17 +306,20 @@ struct Wave {
     // a passer left simply re-reads the last row), which keeps the wait counts exact.
     static constexpr int GB = NQ * (int)sizeof(Chunk) <= 64 ? 2 : 1;
 
-    // Branch-free row load: only the last chunk can run past the row; there the lane re-reads chunk
-    // 0 (in bounds) and the value is replaced by zeros, so no load ever sits inside a branch and the
-    // loads of several rows stay in flight together.
+    // Branch-free row load: only the last TAILS chunks can run past the row; there the lane re-reads
+    // chunk 0 (in bounds) and the value is replaced by zeros, so no load ever sits inside a branch and
+    // the loads of several rows stay in flight together.
     __device__ __forceinline__ void load_vec(Chunk (&v)[NQ], u32 id) const {
         const Chunk* p = (const Chunk*)((const char*)A.vec + (u64)id * A.d * (HALF ? 2 : 4));
 #pragma unroll
-        for (int c = 0; c < NQ - 1; ++c) v[c] = p[c * 64 + lane];
-        Chunk t = p[tail_idx];
-        t.x &= tail_mask; t.y &= tail_mask;
-        if constexpr (VM != 2) { t.z &= tail_mask; t.w &= tail_mask; }
-        v[NQ - 1] = t;
+        for (int c = 0; c < NQ - TAILS; ++c) v[c] = p[c * 64 + lane];
+#pragma unroll
+        for (int t = 0; t < TAILS; ++t) {
+            Chunk x = p[tail_idx[t]];
+            x.x &= tail_mask[t]; x.y &= tail_mask[t];
+            if constexpr (VM != 2) { x.z &= tail_mask[t]; x.w &= tail_mask[t]; }
+            v[NQ - TAILS + t] = x;
+        }
     }
 
     // sum over this lane's elements of fl32(q - x)^2, accumulated in fp64
@@ -503,11 +514,11 @@ struct Wave {
             for (int c = 0; c < NQ; ++c) {
                 const u32 idx = c * 64 + lane;
                 if constexpr (VM == 1) {
-                    const bool in = c < NQ - 1 || idx * 8 < d;
+                    const bool in = c < NQ - TAILS || idx * 8 < d;
                     q[2 * c] = in ? qp[2 * idx] : make_float4(0.f, 0.f, 0.f, 0.f);
                     q[2 * c + 1] = in ? qp[2 * idx + 1] : make_float4(0.f, 0.f, 0.f, 0.f);
                 } else {
-                    q[c] = (c < NQ - 1 || idx * 4 < d) ? qp[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    q[c] = (c < NQ - TAILS || idx * 4 < d) ? qp[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             }
             const float4* tp = (const float4*)(A.tables + (u64)qi * A.Ppad * PAG_NCODE);

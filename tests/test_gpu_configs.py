@@ -96,6 +96,28 @@ def test_large_retrieval_sizes_at_workload_shapes(orc, cfg, n, K, efS, fp16):
     assert np.all(np.diff(gd, axis=1) >= 0)
 
 
+@pytest.mark.parametrize("d", [1152, 1280, 1792, 2304, 2560, 2816])
+@pytest.mark.parametrize("fp16", [False, True])
+def test_row_lengths_between_instantiated_kernels(orc, d, fp16):
+    """Row lengths whose number of per-lane chunks is not itself instantiated (5, 7, 9, 11 chunk rows) or
+    whose last chunk row is only partly filled: the kernel for one more chunk row masks its last two."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_FP16_VECTORS
+    rng = np.random.default_rng(d + int(fp16))
+    n = 400
+    base = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((40, d)).astype(np.float32)
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric="l2", max_degree=16, num_subspaces=16,
+                         ef_construction=60, seed=5, flags=FLAG_FP16_VECTORS if fp16 else 0)
+    ex = gix.export()
+    oix = _oracle_view(orc, ex)
+    for K, efS in ((10, 40), (100, 150)):
+        _parity(orc, gix, oix, q, K, efS)
+    # the last node's row is the last of the store: its distances are right as well
+    ids, dists = gix.search(torch.from_numpy(base[-1:].copy()).cuda(), 1, 400)
+    assert int(ids[0, 0]) == n - 1
+
+
 def test_online_insertion_rounds(orc):
     """Workload 5's structure at reduced size: insertion batches interleaved with query batches."""
     PagIndex = _gpu()
