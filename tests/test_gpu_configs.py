@@ -118,6 +118,47 @@ def test_row_lengths_between_instantiated_kernels(orc, d, fp16):
     assert int(ids[0, 0]) == n - 1
 
 
+def test_seeded_random_shapes(orc):
+    """A seeded sweep over shapes nobody would pick by hand (subspace sizes 4..96, degrees 4..64, odd K,
+    efS from 1 to 2000, both metrics, both stores, working-set overrides): build, export, oracle parity."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_FP16_VECTORS
+    rng = np.random.default_rng(2603)
+    done = 0
+    while done < 14:
+        P = int(rng.choice([1, 2, 4, 8, 12, 16, 32, 48, 64]))
+        d = P * int(rng.choice([4, 8, 12, 20, 24, 40, 48, 96]))
+        if d > 3072 or d % 8:
+            continue
+        deg = int(rng.choice([4, 8, 16, 31, 32, 48, 64]))
+        n = min(int(rng.choice([50, 300, 1500])), max(50, 2_000_000 // d))
+        K = min(n, int(rng.choice([1, 5, 10, 37, 100, 200, 600])))
+        efS = int(rng.choice([1, 10, 50, 200, 700, 2000]))
+        metric = str(rng.choice(["l2", "cos"]))
+        fp16 = bool(rng.integers(0, 2))
+        sb = int(rng.choice([0, 0, 0, max(K, 64), max(K, 300)]))
+        base = rng.standard_normal((n, d)).astype(np.float32)
+        q = rng.standard_normal((24, d)).astype(np.float32)
+        what = "n %d d %d P %d deg %d K %d efS %d %s fp16 %d b %d" % (n, d, P, deg, K, efS, metric, fp16, sb)
+        gix = PagIndex.build(torch.from_numpy(base).cuda(), metric=metric, max_degree=deg, num_subspaces=P,
+                             ef_construction=60, seed=done + 1, flags=FLAG_FP16_VECTORS if fp16 else 0)
+        ex = gix.export()
+        oix = _oracle_view(orc, ex)
+        gix.set_search_options(sb, 0)
+        gi, gd = gix.search(torch.from_numpy(q).cuda(), K, efS)
+        oi, od, _ = oix.search(q, K, efS, b=sb)
+        gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+        assert (gi == oi).mean() >= 0.999, what
+        m = (gi == oi) & np.isfinite(od)
+        assert np.all(np.abs(gd[m] - od[m]) <= 1e-5 * np.abs(od[m]) + 1e-12), what
+        k = min(n, 64)
+        codes, a, c, e2 = oix.recompute_edge_info(0, k)
+        assert np.array_equal(codes, ex["codes"][:k]), what
+        assert np.allclose(a, ex["a"][:k], rtol=3e-7, atol=0), what
+        gix.close()
+        done += 1
+
+
 def test_online_insertion_rounds(orc):
     """Workload 5's structure at reduced size: insertion batches interleaved with query batches."""
     PagIndex = _gpu()
