@@ -147,6 +147,7 @@ int pag_search(const pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uin
  */
 int pag_insert(pag_index* ix, const float* X, uint64_t m);
 
+/* Waits for the index's stream, releases everything the index owns.  NULL is accepted.  Free its searchers first. */
 int pag_free(pag_index* ix);
 
 /* Fills n, d, num_subspaces, max_degree, n_entry, metric of `out` (pointers untouched). */
@@ -158,6 +159,7 @@ int pag_export(const pag_index* ix, pag_arrays* out);
  * listed twice by one node, or an entry id listed twice. */
 int pag_import(const pag_arrays* in, const pag_params* params, pag_index** out);
 
+/* Statistics summed over all searches since the last reset (set out->struct_size first), and the reset. */
 int pag_get_counters(const pag_index* ix, pag_counters* out);
 int pag_reset_counters(pag_index* ix);
 /* Changes search-time settings of an existing index: working-set size (0 = max(10,K)) and PAG_FLAG_* bits. */
