@@ -63,6 +63,50 @@ __device__ __forceinline__ void dist_lds4(const pag_vecs& V, u32 d, const float*
     for (int g = 0; g < 4; ++g) out[g] = (float)pagk::fold_total<4>(tot, g);
 }
 
+// the same for two staged vectors at once: the four rows are fetched once and used twice
+__device__ __forceinline__ void dist_lds4x2(const pag_vecs& V, u32 d, const float* s0, const float* s1, const u32 (&id)[4],
+                                            float (&out0)[4], float (&out1)[4]) {
+    const float4 *q0 = (const float4*)s0, *q1 = (const float4*)s1;
+    double acc0[4] = {0.0, 0.0, 0.0, 0.0}, acc1[4] = {0.0, 0.0, 0.0, 0.0};
+    for (u32 c = threadIdx.x; c < d / 4; c += 64) {
+        const float4 a0 = q0[c], a1 = q1[c];
+        float4 b[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) b[g] = pag_vload4(V, id[g], c);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float dx = a0.x - b[g].x, dy = a0.y - b[g].y, dz = a0.z - b[g].z, dw = a0.w - b[g].w;
+            acc0[g] = __builtin_fma((double)dx, (double)dx, acc0[g]);
+            acc0[g] = __builtin_fma((double)dy, (double)dy, acc0[g]);
+            acc0[g] = __builtin_fma((double)dz, (double)dz, acc0[g]);
+            acc0[g] = __builtin_fma((double)dw, (double)dw, acc0[g]);
+            dx = a1.x - b[g].x; dy = a1.y - b[g].y; dz = a1.z - b[g].z; dw = a1.w - b[g].w;
+            acc1[g] = __builtin_fma((double)dx, (double)dx, acc1[g]);
+            acc1[g] = __builtin_fma((double)dy, (double)dy, acc1[g]);
+            acc1[g] = __builtin_fma((double)dz, (double)dz, acc1[g]);
+            acc1[g] = __builtin_fma((double)dw, (double)dw, acc1[g]);
+        }
+    }
+    const double t0 = pagk::fold_sum<4>(acc0), t1 = pagk::fold_sum<4>(acc1);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) { out0[g] = (float)pagk::fold_total<4>(t0, g); out1[g] = (float)pagk::fold_total<4>(t1, g); }
+}
+
+// squared distance between two vectors staged in LDS, all lanes get the result
+__device__ __forceinline__ float dist_lds_lds(u32 d, const float* s0, const float* s1) {
+    const float4 *q0 = (const float4*)s0, *q1 = (const float4*)s1;
+    double acc = 0.0;
+    for (u32 c = threadIdx.x; c < d / 4; c += 64) {
+        const float4 a = q0[c], b = q1[c];
+        const float dx = a.x - b.x, dy = a.y - b.y, dz = a.z - b.z, dw = a.w - b.w;
+        acc = __builtin_fma((double)dx, (double)dx, acc);
+        acc = __builtin_fma((double)dy, (double)dy, acc);
+        acc = __builtin_fma((double)dz, (double)dz, acc);
+        acc = __builtin_fma((double)dw, (double)dw, acc);
+    }
+    return (float)wave_sum(acc);
+}
+
 __device__ __forceinline__ void stage(const pag_vecs& V, u32 d, u32 id, float* s, int lane) {
     for (u32 c = lane; c < d / 4; c += 64) ((float4*)s)[c] = pag_vload4(V, id, c);
 }
@@ -116,8 +160,8 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
                                                   const u64* __restrict__ pes,
                                                   u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
     extern __shared__ __align__(16) unsigned char smem[];
-    float* sv = (float*)smem;                  // [d] candidate vector
-    u32* kept = (u32*)(sv + L.d);              // [deg]
+    float* sv = (float*)smem;                  // [2][d] candidate vectors
+    u32* kept = (u32*)(sv + 2 * L.d);          // [deg]
     const u32 vi = blockIdx.x;
     if (vi >= m) return;
     // the sorted list lives in HBM: it is read once, front to back, and keeping it out of LDS lets
@@ -131,25 +175,38 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
     u32 nk = 0;
     u32 my_id = PAG_EMPTY;       // lane s holds kept[s]
     u32 my_key = 0;
-    for (u32 ci = 0; ci < nc && nk < L.deg; ++ci) {
-        const u64 k = sorted[ci];
-        const u32 c = (u32)(k & 0xFFFFFFFFull) >> 1;
-        const float dvc = __uint_as_float((u32)(k >> 32));
-        stage(vec, L.d, c, sv, lane);
+    // Candidates are taken two at a time: both are tested against the neighbours kept so far with one
+    // pass over those rows, and the second additionally against the first if that one has just been kept,
+    // which is what testing them one after the other amounts to.
+    float* sv1 = sv + L.d;                     // the second candidate
+    for (u32 ci = 0; ci < nc && nk < L.deg; ci += 2) {
+        const bool two = ci + 1 < nc;
+        const u64 k1 = sorted[ci], k2 = two ? sorted[ci + 1] : k1;
+        const u32 c1 = (u32)(k1 & 0xFFFFFFFFull) >> 1, c2 = (u32)(k2 & 0xFFFFFFFFull) >> 1;
+        const float dv1 = __uint_as_float((u32)(k1 >> 32)), dv2 = __uint_as_float((u32)(k2 >> 32));
+        stage(vec, L.d, c1, sv, lane);
+        stage(vec, L.d, c2, sv1, lane);
         __syncthreads();
-        bool occluded = false;
-        for (u32 s0 = 0; s0 < nk && !occluded; s0 += 4) {
+        bool occ1 = false, occ2 = !two;
+        for (u32 s0 = 0; s0 < nk && !(occ1 && occ2); s0 += 4) {
             u32 sid[4];
-            float dsc[4];
+            float d1[4], d2[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) sid[g] = kept[s0 + g < nk ? s0 + g : nk - 1];
-            dist_lds4(vec, L.d, sv, sid, dsc);
+            for (int g = 0; g < 4; ++g) sid[g] = kept[s0 + g < nk ? s0 + g : nk - 1];   // a repeated last entry changes nothing
+            dist_lds4x2(vec, L.d, sv, sv1, sid, d1, d2);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) occluded = occluded || dsc[g] <= dvc;   // a repeated last entry changes nothing
+            for (int g = 0; g < 4; ++g) { occ1 = occ1 || d1[g] <= dv1; occ2 = occ2 || d2[g] <= dv2; }
         }
-        if (!occluded) {
-            if ((u32)lane == nk) { my_id = c; my_key = (u32)(k >> 32); kept[nk] = c; }
+        if (!occ1) {
+            if ((u32)lane == nk) { my_id = c1; my_key = (u32)(k1 >> 32); kept[nk] = c1; }
             nk++;
+        }
+        if (two && nk < L.deg) {
+            if (!occ1 && !occ2) occ2 = dist_lds_lds(L.d, sv, sv1) <= dv2;
+            if (!occ2) {
+                if ((u32)lane == nk) { my_id = c2; my_key = (u32)(k2 >> 32); kept[nk] = c2; }
+                nk++;
+            }
         }
         __syncthreads();
     }
@@ -396,7 +453,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
                                                            ws.seg_begin, ws.seg_end, 1, 64, s));
         //    RobustPrune -> N_out(v), reverse pairs
         {
-            const u32 plds = L.d * 4 + L.deg * 4;
+            const u32 plds = 2 * L.d * 4 + L.deg * 4;
             hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, (u32)pos, (u32)m,
                                ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
             PAG_HIP(hipGetLastError());
