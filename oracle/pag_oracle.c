@@ -24,8 +24,9 @@
  *   with S_i summed over the subspaces in increasing order.
  *
  * Parity pins: see tests/test_oracle_*.py.  Two parts are "parity unpinned":
- * which traversal the heuristic takes (the hop-synchronous reading below *is*
- * the definition), and the graph the sequential build produces (validated only
+ * which traversal the heuristic takes with the projection test active (the
+ * hop-synchronous reading below *is* the definition; the round mechanics alone
+ * are pinned by runs traced by hand with the test switched off), and the graph the sequential build produces (validated only
  * through recall against brute force).
  */
 #include <math.h>
