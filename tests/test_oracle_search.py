@@ -282,3 +282,41 @@ def test_hand_traced_tfb_rounds(orc):
         assert dists[0].tolist() == [float(x) for x in case["dists"].split()]
         for key in ("hops", "exact", "tests", "passes", "rounds", "rt_over", "rf_over"):
             assert ctr[key] == int(case[key]), (key, ctr[key], case[key])
+
+
+def test_projection_test_inside_the_search(orc):
+    """The PRT-TFB decision taken inside Alg. 2, on the hand-computed geometry of
+    tests/golden/worked_example.txt: one neighbour passes (estimate 7.2 < threshold 10), its mirror image
+    fails (estimate 40.8) and is never computed; with the test off both are."""
+    import os
+    g = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "worked_example.txt")):
+        line = line.split("#")[0].split()
+        if len(line) == 2:
+            g[line[0]] = float(line[1])
+    P, d = 2, 4
+    cb = np.zeros((P, 16, 2), np.float32)
+    axes = np.array([[1, 0], [-1, 0], [0, 1], [0, -1]], np.float32) / np.float32(np.sqrt(2.0))
+    for l in range(P):
+        cb[l, :4] = axes
+        cb[l, 4:] = axes[0]              # the other slots repeat index 0: they never win the argmax
+    vec = np.array([[0, 0, 0, 0], [3, 1, 0, -2], [-3, -1, 0, 2]], np.float32)     # u, w, w'
+    adj = np.full((3, 2), orc.EMPTY, np.uint32)
+    adj[0] = [1, 2]
+    ix = orc.OracleIndex(vec, adj, np.zeros((3, 2), np.float32), np.zeros((3, 2), np.float32),
+                         np.zeros((3, 2), np.float32), np.zeros((3, 2, P), np.uint8), np.eye(4, dtype=np.float32), cb,
+                         np.array([0], np.uint32))
+    codes, a, c, e2 = ix.recompute_edge_info()
+    ix.codes[:], ix.a[:], ix.c[:], ix.e2[:] = codes, a, c, e2
+    assert codes[0].tolist() == [[0, 3], [1, 2]]
+    q = np.array([[2, 2, 1, -1]], np.float32)
+    _, T = ix.prepare(q)
+    est = [orc.est32(10.0, a[0, s], c[0, s], orc.S32(T[0], codes[0, s])) for s in range(2)]
+    assert est[0] == pytest.approx(7.2, rel=1e-6) and est[1] == pytest.approx(g["search_est_w2"], rel=1e-6)
+    ids, dists, ctr = ix.search(q, 1, 1, b=1)
+    assert ids[0, 0] == int(g["search_result_id"]) and dists[0, 0] == g["search_result_dist"]
+    assert ctr["exact"] == int(g["search_exact_count"])
+    assert ctr["tests"] == int(g["search_tests"]) and ctr["passes"] == int(g["search_passes"])
+    ids, dists, ctr = ix.search(q, 1, 1, b=1, flags=orc.NO_PRT)
+    assert ids[0, 0] == int(g["search_result_id"]) and ctr["exact"] == int(g["search_exact_count_without_test"])
+    assert orc.sqdist64(q[0], vec[2]) == g["search_exact_w2"]
