@@ -25,9 +25,11 @@
  *
  * Parity pins: see tests/test_oracle_*.py.  Two parts are "parity unpinned":
  * which traversal the heuristic takes with the projection test active (the
- * hop-synchronous reading below *is* the definition; the round mechanics alone
- * are pinned by runs traced by hand with the test switched off), and the graph the sequential build produces (validated only
- * through recall against brute force).
+ * hop-synchronous reading below *is* the definition; what is pinned are runs
+ * traced by hand -- the round mechanics with the test switched off, the same
+ * with the test on where its estimate is exact (collinear points), and one hop
+ * of a hand-computed general case), and the graph the sequential build
+ * produces (validated only through recall against brute force).
  */
 #include <math.h>
 #include <stdint.h>

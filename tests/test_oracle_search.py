@@ -259,25 +259,37 @@ def _read_hand_trace():
 
 def test_hand_traced_tfb_rounds(orc):
     """Alg. 2's round mechanics (eviction to R_T, false positives to R_F, FIFO overflow, refill of W with
-    visited flags kept, termination) against traces worked out by hand: tests/golden/tfb_hand_trace.txt."""
+    visited flags kept, termination) against traces worked out by hand: tests/golden/tfb_hand_trace.txt.
+    Two of the traces run with the routing test on, on a geometry where its estimate is exact."""
     common, cases = _read_hand_trace()
-    pos = np.array(common["positions"].split(), dtype=np.float32)
-    n, b, K = len(pos), int(common["b"]), int(common["K"])
-    vec = np.zeros((n, 2), np.float32)
-    vec[:, 0] = pos
+    b, K = int(common["b"]), int(common["K"])
     deg, P = 2, 1
-    assert cases
+    axis = np.zeros((P, 16, 2), np.float32)           # +e1, -e1, +e2, -e2 at norm 1/sqrt(P) = 1; other slots repeat +e1
+    axis[0, :, 0] = 1.0
+    axis[0, 1] = [-1, 0]
+    axis[0, 2] = [0, 1]
+    axis[0, 3] = [0, -1]
+    assert len(cases) == 4 and sum(c.get("prt") == "on" for c in cases) == 2
     for case in cases:
+        pos = np.array(case.get("positions", common["positions"]).split(), dtype=np.float32)
+        n = len(pos)
+        vec = np.zeros((n, 2), np.float32)
+        vec[:, 0] = pos
         adj = np.full((n, deg), orc.EMPTY, np.uint32)
         for item in case["adjacency"].split():
             u, nb = item.split(":")
             nb = [int(x) for x in nb.split(",")]
             adj[int(u), :len(nb)] = nb
+        prt = case.get("prt") == "on"
         ix = orc.OracleIndex(vec, adj, np.zeros((n, deg), np.float32), np.zeros((n, deg), np.float32),
                              np.zeros((n, deg), np.float32), np.zeros((n, deg, P), np.uint8),
-                             np.eye(2, dtype=np.float32), orc.make_codebooks(2, P, 1),
+                             np.eye(2, dtype=np.float32), axis if prt else orc.make_codebooks(2, P, 1),
                              np.arange(n, dtype=np.uint32))
-        ids, dists, ctr = ix.search(np.zeros((1, 2), np.float32), K, int(case["efS"]), b=b, flags=orc.NO_PRT)
+        if prt:
+            codes, a, c, e2 = ix.recompute_edge_info()
+            ix.codes[:], ix.a[:], ix.c[:], ix.e2[:] = codes, a, c, e2
+        ids, dists, ctr = ix.search(np.zeros((1, 2), np.float32), K, int(case["efS"]), b=b,
+                                    flags=0 if prt else orc.NO_PRT)
         assert ids[0].tolist() == [int(x) for x in case["ids"].split()]
         assert dists[0].tolist() == [float(x) for x in case["dists"].split()]
         for key in ("hops", "exact", "tests", "passes", "rounds", "rt_over", "rf_over"):
