@@ -269,7 +269,7 @@ def test_hand_traced_tfb_rounds(orc):
     axis[0, 1] = [-1, 0]
     axis[0, 2] = [0, 1]
     axis[0, 3] = [0, -1]
-    assert len(cases) == 4 and sum(c.get("prt") == "on" for c in cases) == 2
+    assert len(cases) == 5 and sum(c.get("prt") == "on" for c in cases) == 3
     for case in cases:
         pos = np.array(case.get("positions", common["positions"]).split(), dtype=np.float32)
         n = len(pos)
@@ -289,7 +289,7 @@ def test_hand_traced_tfb_rounds(orc):
             codes, a, c, e2 = ix.recompute_edge_info()
             ix.codes[:], ix.a[:], ix.c[:], ix.e2[:] = codes, a, c, e2
         ids, dists, ctr = ix.search(np.zeros((1, 2), np.float32), K, int(case["efS"]), b=b,
-                                    flags=0 if prt else orc.NO_PRT)
+                                    flags=(orc.LITERAL if case.get("literal") == "on" else 0) if prt else orc.NO_PRT)
         assert ids[0].tolist() == [int(x) for x in case["ids"].split()]
         assert dists[0].tolist() == [float(x) for x in case["dists"].split()]
         for key in ("hops", "exact", "tests", "passes", "rounds", "rt_over", "rf_over"):
