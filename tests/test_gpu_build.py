@@ -271,3 +271,38 @@ def test_fp16_vector_store(orc, cfg1_small, cfg1_oracle_index):
     gix3.insert(torch.from_numpy(base[2000:]).cuda())
     gi3, _ = gix3.search(qd, w.K, 64)
     assert wl.recall_at_k(gi3.cpu().numpy(), gt) >= 0.95
+
+
+def test_freeing_returns_device_memory(cfg1_small):
+    """pag_free / pag_searcher_free give back everything the library allocated: after a warm-up cycle,
+    five more build + insert + search + searcher cycles leave the device's free memory where it was."""
+    PagIndex = _gpu()
+    w, base, q, gt, gtk = cfg1_small
+    bd = torch.from_numpy(base).cuda()
+    qd = torch.from_numpy(q).cuda()
+    out = (torch.empty((qd.shape[0], w.K), dtype=torch.int64, device="cuda"),
+           torch.empty((qd.shape[0], w.K), dtype=torch.float32, device="cuda"))
+
+    side = torch.cuda.Stream()                           # one stream for every searcher: a new stream takes device memory of its own
+
+    def cycle(seed):
+        gix = PagIndex.build(bd[:3000].contiguous(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                             ef_construction=100, seed=seed, capacity=4000)
+        gix.insert(bd[3000:4000].contiguous())
+        gix.search(qd, w.K, 64, out=out)
+        gix.search(qd, w.K, 2048, out=out)               # long-search regime: bitmaps in use
+        s = gix.searcher(stream=side)
+        s.search(qd, w.K, 64, out=out)
+        s.close()
+        ex = gix.export()
+        gix.close()
+        return ex["adj"].shape
+
+    cycle(1)
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    for i in range(5):
+        cycle(2 + i)
+    torch.cuda.synchronize()
+    free1 = torch.cuda.mem_get_info()[0]
+    assert free0 - free1 <= (2 << 20), (free0, free1)
