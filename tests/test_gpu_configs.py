@@ -1,7 +1,7 @@
 """Search parity at the true shapes of the other workloads (d, K, degree, subspaces, metric, OOD
-queries, online insertion) on reduced n, and at the full size of the benchmark workload on a sample
-of the queries.  Index: built by the GPU library, exported, validated by the oracle, then searched
-by both sides."""
+queries, online insertion) on reduced n with every query checked, and at the full size of every
+workload (n, d, query-batch size as configured) on a sample of the queries.  Index: built by the GPU
+library, exported, validated by the oracle, then searched by both sides."""
 import dataclasses
 
 import numpy as np
@@ -199,7 +199,7 @@ def test_full_size_benchmark_workload(orc):
     assert (ref == ex["vectors"][rows]).mean() >= 0.9999
     _check_edge_info(orc, oix, ex, (0, 500_000, w.n - 64))
     sample = np.arange(0, w.nq, 40)                      # 250 queries
-    for efS in (64, 512):
+    for efS in (64, 512, 1408):                          # 1408: the benchmark's operating point (bitmap + Bloom seen set)
         gi, gd, oi = _parity(orc, gix, oix, q, w.K, efS, sample=sample)
         assert abs(wl.recall_at_k(gi[sample], gt[sample]) - wl.recall_at_k(oi, gt[sample])) <= 0.002
         # property that holds for every query at any size: ascending keys, valid distinct ids
@@ -209,3 +209,33 @@ def test_full_size_benchmark_workload(orc):
     # sampled outputs checked one by one: the reported key is the true 1 - <q, x>
     ip = np.einsum("qkd,qd->qk", base[gi[sample]].astype(np.float64), q[sample].astype(np.float64))
     assert np.allclose(gd[sample], 1.0 - ip, atol=5e-6)
+
+
+@pytest.mark.parametrize("cfg,efS", [(3, (128, 1024)), (4, (64, 640)), (5, (64, 1536))])
+def test_full_size_other_workloads(orc, cfg, efS):
+    """The other workloads at their full n, d, degree, subspaces, K and query-batch size (a light efC keeps
+    the build short): the oracle searches the exported index for a sample of the queries, at a short and
+    at a long search length."""
+    PagIndex = _gpu()
+    w = wl.workload(cfg)
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    metric = {0: "l2", 1: "ip", 2: "cos"}[w.metric]
+    base_d = torch.from_numpy(base).cuda()
+    gix = PagIndex.build(base_d, metric=metric, max_degree=w.deg, num_subspaces=w.P, ef_construction=100, seed=cfg)
+    del base_d
+    ex = gix.export()
+    oix = _oracle_view(orc, ex)
+    rows = np.arange(0, w.n, 250007)
+    src = base[rows].astype(np.float64)
+    if metric == "cos":
+        src = src / np.linalg.norm(src, axis=1, keepdims=True)
+    ref = src @ ex["rotation"].astype(np.float64).T
+    assert np.allclose(ex["vectors"][rows], ref, rtol=0, atol=2e-6)
+    _check_edge_info(orc, oix, ex, (0, w.n // 2, w.n - 64))
+    sample = np.arange(0, w.nq, w.nq // 100)             # 100 queries
+    for e in efS:
+        gi, gd, oi = _parity(orc, gix, oix, q, w.K, e, sample=sample)
+        assert np.all(np.diff(gd, axis=1) >= 0) and gi.min() >= 0 and gi.max() < w.n
+        srt = np.sort(gi, axis=1)
+        assert not np.any(srt[:, 1:] == srt[:, :-1])
+    gix.close()
