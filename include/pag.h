@@ -124,7 +124,11 @@ typedef struct {
 /*
  * pag_build (Alg. 1, Step 1, batch-synchronous): creates an index over the n
  * vectors D (dev, float32 [n*d]).  D is normalised (PAG_COS), rotated by Q and
- * copied into the index.  *out receives the handle.
+ * copied into the index.  *out receives the handle.  Node i is row i of D.  The
+ * nodes are linked in batches drawn from a shuffle of the ids that
+ * pag_params.seed fixes, so the order in which the rows arrive (sorted by
+ * cluster, source or time) does not shape the graph; the first 1024 nodes of
+ * that shuffle are the entry nodes.
  */
 int pag_build(const float* D, uint64_t n, uint32_t d, const pag_params* params, pag_index** out);
 
@@ -142,8 +146,11 @@ int pag_search(const pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uin
 
 /*
  * pag_insert (online insertion, Sec. 4.1): appends the m vectors X (dev,
- * float32 [m*d]); they receive ids n .. n+m-1.  PAG_ECAPACITY if n + m exceeds
- * pag_params.capacity.
+ * float32 [m*d]); they receive ids n .. n+m-1 and are linked in shuffled
+ * batches like the vectors of pag_build.  The vectors of one batch do not see
+ * each other: a call whose vectors all lie in a region the index does not
+ * cover yet links them better with a small pag_params.insert_subbatch.
+ * PAG_ECAPACITY if n + m exceeds pag_params.capacity.
  */
 int pag_insert(pag_index* ix, const float* X, uint64_t m);
 

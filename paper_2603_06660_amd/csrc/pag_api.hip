@@ -210,16 +210,6 @@ pag_index* new_index(const pag_params* p, uint32_t d) {
     return ix;
 }
 
-int set_entry_list(pag_index* ix) {
-    const u32 ne = (u32)std::min<u64>(ix->n, 1024);
-    std::vector<u32> e(ne ? ne : 1);
-    for (u32 i = 0; i < ne; ++i) e[i] = i;
-    PAG_HIP(hipMemcpyAsync(ix->entry, e.data(), ne * sizeof(u32), hipMemcpyHostToDevice, ix->stream));
-    PAG_HIP(hipStreamSynchronize(ix->stream));
-    ix->n_entry = ne;
-    return PAG_OK;
-}
-
 // normalise (COS) + rotate `rows` raw vectors X (dev) into rows [row0, row0 + rows) of the store
 int ingest(pag_index* ix, const float* X, u64 rows, u64 row0) {
     const u32 d = ix->L.d;
@@ -290,7 +280,6 @@ extern "C" int pag_build(const float* D, uint64_t n, uint32_t d, const pag_param
     ix->n = 0;
     if ((rc = pag_build_range(ix, 0, n))) { pag_free(ix); return rc; }
     ix->n = n;
-    if ((rc = set_entry_list(ix))) { pag_free(ix); return rc; }
     ix->last_build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     *out = ix;
     return PAG_OK;
@@ -308,7 +297,6 @@ extern "C" int pag_insert(pag_index* ix, const float* X, uint64_t m) {
     if ((rc = pag_build_range(ix, ix->n, ix->n + m))) return rc;
     // publish: every kernel of the insertion has finished (pag_build_range synchronises), searchers may now see the nodes
     __atomic_store_n(&ix->n, ix->n + m, __ATOMIC_RELEASE);
-    if ((rc = set_entry_list(ix))) return rc;
     ix->last_build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     return PAG_OK;
 }

@@ -111,32 +111,41 @@ __device__ __forceinline__ void stage(const pag_vecs& V, u32 d, u32 id, float* s
     for (u32 c = lane; c < d / 4; c += 64) ((float4*)s)[c] = pag_vload4(V, id, c);
 }
 
-// ---- initial nodes: each of the first n_init nodes is linked to its nearest min(deg, n_init-1) peers ----
+// ---- initial nodes: each of the n_init listed nodes is linked to its nearest min(deg, n_init-1) peers ----
 __global__ void __launch_bounds__(64) k_init_clique(pag_vecs vec, uint8_t* __restrict__ recs,
-                                                    pag_layout L, u32 n_init) {
+                                                    pag_layout L, const u32* __restrict__ nodes, u32 n_init) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sv = (float*)smem;                       // [d]
     u64* keys = (u64*)(sv + L.d);                   // [n_init]
     u64* sorted = keys + n_init;                    // [n_init]
-    const u32 v = blockIdx.x;
+    const u32 vi = blockIdx.x;
+    const u32 v = nodes[vi];
     const int lane = threadIdx.x;
     stage(vec, L.d, v, sv, lane);
     __syncthreads();
     for (u32 o = 0; o < n_init; ++o) {
-        const float dist = dist_lds(vec, L.d, sv, o, lane);
-        if (lane == 0) keys[o] = o == v ? PAG_KEY_INVALID : (((u64)__float_as_uint(dist) << 32) | o);
+        const u32 w = nodes[o];
+        const float dist = dist_lds(vec, L.d, sv, w, lane);
+        if (lane == 0) keys[o] = o == vi ? PAG_KEY_INVALID : (((u64)__float_as_uint(dist) << 32) | w);
     }
     __syncthreads();
     for (u32 i = lane; i < n_init; i += 64) {
         const u64 k = keys[i];
         u32 r = 0;
-        for (u32 j = 0; j < n_init; ++j) r += (keys[j] < k || (keys[j] == k && j < i)) ? 1u : 0u;
+        for (u32 j = 0; j < n_init; ++j) r += (keys[j] < k) ? 1u : 0u;     // keys are distinct: they carry the node id
         sorted[r] = k;
     }
     __syncthreads();
     u32* ids = (u32*)(recs + (u64)v * L.rec_bytes);
     const u32 take = n_init - 1 < L.deg ? n_init - 1 : L.deg;
     if ((u32)lane < L.deg) ids[lane] = (u32)lane < take ? (u32)(sorted[lane] & 0xFFFFFFFFull) : PAG_EMPTY;
+}
+
+// rows of the listed nodes, widened to fp32, gathered into one contiguous block (the batch's queries)
+__global__ void __launch_bounds__(64) k_gather_rows(pag_vecs vec, u32 d, const u32* __restrict__ nodes, float* __restrict__ out) {
+    const u32 v = nodes[blockIdx.x];
+    float4* o = (float4*)(out + (u64)blockIdx.x * d);
+    for (u32 c = threadIdx.x; c < d / 4; c += 64) o[c] = pag_vload4(vec, v, c);
 }
 
 // segment bounds of the per-node candidate lists for the segmented sort
@@ -155,7 +164,7 @@ __global__ void k_cand_segments(const u32* __restrict__ cand_cnt, u32 m, u32 can
 // already kept s has ||s - c|| <= ||v - c||.  Writes N_out(v) into v's record and one reverse
 // pair per kept neighbour: key = target << 32 | dist bits, value = v.
 __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restrict__ recs,
-                                                  pag_layout L, u32 node0, u32 m,
+                                                  pag_layout L, const u32* __restrict__ nodes, u32 m,
                                                   const u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
                                                   const u64* __restrict__ pes,
                                                   u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
@@ -168,7 +177,7 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
     // many waves hide each other's row-fetch latency
     const u64* sorted = cand_sorted + (u64)vi * cand_cap;   // ascending by (dist, id); bit 0 is the visited flag
     const int lane = threadIdx.x;
-    const u32 v = node0 + vi;
+    const u32 v = nodes[vi];
     u32 nc = cand_cnt[vi];
     if (nc > cand_cap) nc = cand_cap;
     if (nc > efC) nc = efC;
@@ -341,11 +350,12 @@ struct BuildWs {
     u64* cand = nullptr; u64* cand_sorted = nullptr; u32* cand_cnt = nullptr; u64* pes = nullptr;
     u64 *rk_in = nullptr, *rk_out = nullptr; u32 *rv_in = nullptr, *rv_out = nullptr;
     u32* edges = nullptr; u32* n_edges = nullptr;
+    u32* order = nullptr;
     void* sort_tmp = nullptr; size_t sort_bytes = 0;
     int *seg_begin = nullptr, *seg_end = nullptr;
     void* seg_tmp = nullptr; size_t seg_bytes = 0;
     ~BuildWs() {
-        void* p[] = { cand, cand_sorted, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, sort_tmp, seg_begin, seg_end, seg_tmp };
+        void* p[] = { cand, cand_sorted, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, order, sort_tmp, seg_begin, seg_end, seg_tmp };
         for (void* x : p) if (x) (void)hipFree(x);
     }
 };
@@ -358,6 +368,19 @@ struct BuildWs {
 
 }  // namespace
 
+// splitmix64: the generator behind the insertion order
+static inline u64 next_random(u64& state) {
+    u64 z = (state += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Inserts the nodes [n_begin, n_end), whose rows are already in the store, into the graph.  They are
+// taken in a pseudo-random order fixed by the index seed, not in id order: the nodes of one batch do
+// not see each other, so a batch of consecutive ids of an input that arrives sorted (by cluster, by
+// source, by time) would hold exactly the points that should have become each other's neighbours;
+// and the entry list, the first 1024 nodes of the order, would sit in one corner of the data.
 int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     if (n_end <= n_begin) return PAG_OK;
     const pag_layout& L = ix->L;
@@ -366,26 +389,43 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     const u32 Rmax = std::max<u32>(1, (ix->efC + b - 1) / b);
     const u32 cand_cap = Rmax * b;
     int rc;
-    u64 pos = n_begin;
+    const u64 count = n_end - n_begin;
+    BuildWs ws;
+    {
+        std::vector<u32> order(count);
+        for (u64 i = 0; i < count; ++i) order[i] = (u32)(n_begin + i);
+        u64 state = ix->seed ^ (0xA0761D6478BD642Full * (n_begin + 1));
+        for (u64 i = count - 1; i > 0; --i) {                 // Fisher-Yates
+            const u64 j = next_random(state) % (i + 1);
+            std::swap(order[i], order[j]);
+        }
+        PAG_ALLOC(ws.order, count * 4);
+        PAG_HIP(hipMemcpyAsync(ws.order, order.data(), count * 4, hipMemcpyHostToDevice, s));
+        // the entry list grows with the first nodes of the order until it holds 1024
+        const u32 have = n_begin == 0 ? 0u : ix->n_entry;
+        if (have < 1024) {
+            const u32 add = (u32)std::min<u64>(count, 1024 - have);
+            PAG_HIP(hipMemcpyAsync(ix->entry + have, order.data(), add * 4, hipMemcpyHostToDevice, s));
+        }
+        if (n_begin == 0) ix->n_entry = 0;
+        PAG_HIP(hipStreamSynchronize(s));                    // `order` (host) is released here
+    }
+    const u32 entry_before = ix->n_entry;
+    u64 done = 0;                                            // nodes of the range inserted so far
     if (n_begin == 0) {
         const u32 n_init = (u32)std::min<u64>(n_end, b);
         if (n_init > 1) {
             const u32 lds = L.d * 4 + 2 * n_init * 8;
-            hipLaunchKernelGGL(k_init_clique, dim3(n_init), dim3(64), lds, s, pag_vecs_of(ix), ix->rec, L, n_init);
+            hipLaunchKernelGGL(k_init_clique, dim3(n_init), dim3(64), lds, s, pag_vecs_of(ix), ix->rec, L, ws.order, n_init);
             PAG_HIP(hipGetLastError());
-            if ((rc = pag_launch_edge_info_nodes(s, ix, 0, n_init, ix->rec, ix->e2, 0))) return rc;
+            if ((rc = pag_launch_edge_info_of(s, ix, ws.order, n_init))) return rc;
         }
-        pos = n_init;
-        // the search kernel reads entry ids from device memory: ids 0 .. min(n, 1024) - 1
-        std::vector<u32> e(1024);
-        for (u32 i = 0; i < 1024; ++i) e[i] = i;
-        PAG_HIP(hipMemcpyAsync(ix->entry, e.data(), 1024 * 4, hipMemcpyHostToDevice, s));
-        PAG_HIP(hipStreamSynchronize(s));
+        done = n_init;
     }
-    if (pos >= n_end) { PAG_HIP(hipStreamSynchronize(s)); return PAG_OK; }
+    ix->n_entry = (u32)std::min<u64>(entry_before + done, 1024);
+    if (done >= count) { PAG_HIP(hipStreamSynchronize(s)); return PAG_OK; }
 
     u64 max_batch = ix->subbatch ? ix->subbatch : std::min<u64>(16384, std::max<u64>(1024, n_end / 50));
-    BuildWs ws;
     PAG_ALLOC(ws.cand, max_batch * cand_cap * 8);
     PAG_ALLOC(ws.cand_sorted, max_batch * cand_cap * 8);
     PAG_ALLOC(ws.cand_cnt, max_batch * 4);
@@ -407,7 +447,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     PAG_HIP(hipcub::DeviceSegmentedRadixSort::SortKeys(nullptr, ws.seg_bytes, ws.cand, ws.cand_sorted, (int)(max_batch * cand_cap),
                                                        (int)max_batch, ws.seg_begin, ws.seg_end, 1, 64, s));
     PAG_ALLOC(ws.seg_tmp, ws.seg_bytes);
-    if (ix->vec_half && ix->ws_qrot_cap < max_batch * L.d) {
+    if (ix->ws_qrot_cap < max_batch * L.d) {            // the rows of a batch, gathered: its queries
         if (ix->ws_qrot) (void)hipFree(ix->ws_qrot);
         ix->ws_qrot = nullptr; ix->ws_qrot_cap = 0;
         PAG_ALLOC(ix->ws_qrot, max_batch * L.d * 4);
@@ -422,23 +462,22 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
             ix->ws_tab_cap = need;
         }
     }
-    while (pos < n_end) {
-        u64 m = std::min<u64>(n_end - pos, max_batch);
-        m = std::min<u64>(m, std::max<u64>(1, pos / 2));
-        // 1. projection tables of the new nodes (they are their own queries, already rotated)
-        // the new nodes are their own queries; a 16-bit store is widened into the query workspace
-        const float* qrot = (const float*)ix->vec + pos * L.d;
-        if (ix->vec_half) {
-            if ((rc = pag_launch_convert(s, (const __half*)ix->vec + pos * L.d, 1, ix->ws_qrot, 0, m * L.d))) return rc;
-            qrot = ix->ws_qrot;
-        }
+    while (done < count) {
+        const u64 graph = n_begin + done;                  // nodes in the graph so far
+        u64 m = std::min<u64>(count - done, max_batch);
+        m = std::min<u64>(m, std::max<u64>(1, graph / 2));
+        const u32* nodes = ws.order + done;
+        // 1. the new nodes are their own queries (already rotated): rows gathered and widened to fp32, then their tables
+        hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)m), dim3(64), 0, s, pag_vecs_of(ix), L.d, nodes, ix->ws_qrot);
+        PAG_HIP(hipGetLastError());
+        const float* qrot = ix->ws_qrot;
         if ((rc = pag_launch_tables(s, qrot, m, L, ix->cb, ix->ws_tab))) return rc;
-        // 2. PRT-TFB search of the graph of nodes [0, pos)
+        // 2. PRT-TFB search of the graph built so far.  Nodes that are not inserted yet have empty records and no
+        //    in-edges, and the entry list holds inserted nodes only, so they cannot be reached.
         SearchArgs a;
         u32 lds = 0;
         int grid = 0;
-        ix->n_entry = (u32)std::min<u64>(pos, 1024);
-        if ((rc = pag_search_common(ix, b, ix->efC, pos, &a, &lds, &grid))) return rc;
+        if ((rc = pag_search_common(ix, b, ix->efC, n_end, &a, &lds, &grid))) return rc;
         a.qrot = qrot; a.tables = ix->ws_tab; a.nq = (u32)m; a.K = b;
         a.flags &= ~(u32)PAG_FLAG_NO_PRT;          // indexing always runs with the projection test on
         a.cand = ws.cand; a.cand_cnt = ws.cand_cnt; a.cand_cap = cand_cap;
@@ -454,7 +493,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         //    RobustPrune -> N_out(v), reverse pairs
         {
             const u32 plds = 2 * L.d * 4 + L.deg * 4;
-            hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, (u32)pos, (u32)m,
+            hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, nodes, (u32)m,
                                ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
             PAG_HIP(hipGetLastError());
         }
@@ -468,12 +507,13 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
                            ws.rv_out, n_pairs, ws.edges, ws.n_edges);
         PAG_HIP(hipGetLastError());
         // 6. inference information of the new forward edges and of every changed reverse slot
-        if ((rc = pag_launch_edge_info_nodes(s, ix, pos, pos + m, ix->rec, ix->e2, 0))) return rc;
+        if ((rc = pag_launch_edge_info_of(s, ix, nodes, m))) return rc;
         u32 n_edges = 0;
         PAG_HIP(hipMemcpyAsync(&n_edges, ws.n_edges, 4, hipMemcpyDeviceToHost, s));
         PAG_HIP(hipStreamSynchronize(s));
         if ((rc = pag_launch_edge_info_list(s, ix, ws.edges, n_edges))) return rc;
-        pos += m;
+        done += m;
+        ix->n_entry = (u32)std::min<u64>(entry_before + done, 1024);
     }
     PAG_HIP(hipStreamSynchronize(s));
     return PAG_OK;

@@ -147,6 +147,7 @@ int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begi
 int pag_launch_row_reads(hipStream_t s, const pag_index* ix, u64 rows, u64 stride, u32* sink, int grid);
 int pag_launch_hop_traffic(hipStream_t s, const pag_index* ix, u64 hops, u32* bitmap, u64 bitmap_words, u32* sink, int grid);
 int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edge_list, u64 n_edges);
+int pag_launch_edge_info_of(hipStream_t s, const pag_index* ix, const u32* nodes, u64 m);   // every slot of m listed nodes (device ids)
 
 int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid);
 inline pag_vecs pag_vecs_of(const pag_index* ix) { return pag_vecs{ ix->vec, ix->L.d, ix->vec_half }; }

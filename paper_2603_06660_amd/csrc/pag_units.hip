@@ -76,7 +76,7 @@ __global__ void __launch_bounds__(64) k_screen(const uint8_t* __restrict__ recs,
 __global__ void __launch_bounds__(64) k_edge_info(pag_vecs V, uint8_t* __restrict__ recs,
                                                   float* __restrict__ e2_out, pag_layout L,
                                                   const float* __restrict__ cb, const u32* __restrict__ edges,
-                                                  u64 n_edges, u64 node_begin, u64 out_base) {
+                                                  u64 n_edges, const u32* __restrict__ nodes, u64 node_begin, u64 out_base) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* diff = (float*)smem;               // [d]
     float* uu = diff + L.d;                   // [d]
@@ -90,7 +90,8 @@ __global__ void __launch_bounds__(64) k_edge_info(pag_vecs V, uint8_t* __restric
         u = edges[2 * (u64)blockIdx.x];
         slot = edges[2 * (u64)blockIdx.x + 1];
     } else {
-        u = (u32)(node_begin + blockIdx.x / L.deg);
+        // every slot of a listed node, or of the node range that starts at node_begin
+        u = nodes ? nodes[blockIdx.x / L.deg] : (u32)(node_begin + blockIdx.x / L.deg);
         slot = blockIdx.x % L.deg;
     }
     uint8_t* rec = recs + ((u64)u - out_base) * L.rec_bytes;
@@ -258,7 +259,7 @@ int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begi
         const u64 ne = nb + nodes_per < node_end ? nb + nodes_per : node_end;
         if (nb >= node_end) break;
         hipLaunchKernelGGL(k_edge_info, dim3((unsigned)((ne - nb) * ix->L.deg)), dim3(64), edge_info_lds(ix->L), s,
-                           pag_vecs_of(ix), recs, e2, ix->L, ix->cb, (const u32*)nullptr, 0ull, nb, out_base);
+                           pag_vecs_of(ix), recs, e2, ix->L, ix->cb, (const u32*)nullptr, 0ull, (const u32*)nullptr, nb, out_base);
     }
     PAG_HIP(hipGetLastError());
     return PAG_OK;
@@ -267,7 +268,15 @@ int pag_launch_edge_info_nodes(hipStream_t s, const pag_index* ix, u64 node_begi
 int pag_launch_edge_info_list(hipStream_t s, const pag_index* ix, const u32* edge_list, u64 n_edges) {
     if (n_edges == 0) return PAG_OK;
     hipLaunchKernelGGL(k_edge_info, dim3((unsigned)n_edges), dim3(64), edge_info_lds(ix->L), s, pag_vecs_of(ix), ix->rec,
-                       ix->e2, ix->L, ix->cb, edge_list, n_edges, 0ull, 0ull);
+                       ix->e2, ix->L, ix->cb, edge_list, n_edges, (const u32*)nullptr, 0ull, 0ull);
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
+}
+
+int pag_launch_edge_info_of(hipStream_t s, const pag_index* ix, const u32* nodes, u64 m) {
+    if (m == 0) return PAG_OK;
+    hipLaunchKernelGGL(k_edge_info, dim3((unsigned)(m * ix->L.deg)), dim3(64), edge_info_lds(ix->L), s, pag_vecs_of(ix), ix->rec,
+                       ix->e2, ix->L, ix->cb, (const u32*)nullptr, 0ull, nodes, 0ull, 0ull);
     PAG_HIP(hipGetLastError());
     return PAG_OK;
 }

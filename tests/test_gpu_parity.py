@@ -235,6 +235,59 @@ def test_edge_cases(orc):
             PagIndex.from_arrays(oix.vec, adj, oix.a, oix.c, oix.e2, oix.codes, oix.rot, oix.cb, entry, metric="l2")
 
 
+def test_unreachable_nodes_and_duplicate_vectors(orc):
+    """Degenerate inputs.  (a) A graph of two components with every entry node in the first: the second
+    component is never reached and the result slots beyond the first component hold (-1, +inf).
+    (b) A base set whose last quarter repeats its first quarter (zero-length edges: a = c = 0, Sec. 3.1's
+    angles are undefined there; equal keys are ordered by id): GPU build, export, oracle-validated
+    inference information, search parity."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_NO_PRT
+    rng = np.random.default_rng(77)
+    n, d, deg, P = 40, 16, 4, 2
+    vec = rng.standard_normal((n, d)).astype(np.float32)
+    adj = np.full((n, deg), orc.EMPTY, np.uint32)
+    for i in range(n):
+        comp, k = divmod(i, 20)
+        adj[i] = [comp * 20 + (k + s) % 20 for s in (1, 2, 19, 18)]
+    z = lambda *shape: np.zeros(shape, np.float32)
+    oix = orc.OracleIndex(vec, adj, z(n, deg), z(n, deg), z(n, deg), np.zeros((n, deg, P), np.uint8),
+                          np.eye(d, dtype=np.float32), orc.make_codebooks(d, P, 5), np.arange(10, dtype=np.uint32))
+    codes, a, c, e2 = oix.recompute_edge_info()
+    oix.codes[:], oix.a[:], oix.c[:], oix.e2[:] = codes, a, c, e2
+    gix = _import(PagIndex, oix)
+    q = rng.standard_normal((9, d)).astype(np.float32)
+    for flags in (0, FLAG_NO_PRT):
+        gix.set_search_options(0, flags)
+        qd = torch.from_numpy(q).cuda()
+        gi, gd = gix.search(qd, 30, 90)
+        gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+        oi, od, _ = oix.search(q, 30, 90, flags=orc.NO_PRT if flags else 0)
+        assert np.array_equal(gi, oi)
+        assert np.all(gi[:, 20:] == -1) and np.all(np.isinf(gd[:, 20:])) and np.all(gi < 20)
+        if flags:
+            assert np.all(gi[:, :20] >= 0)                  # without the test the whole component is visited
+            assert np.array_equal(np.sort(gi[:, :20], axis=1), np.tile(np.arange(20), (9, 1)))
+    # (b) duplicates
+    base = rng.standard_normal((2000, 32)).astype(np.float32)
+    base[1500:] = base[:500]                               # far apart in id: a twin is in the graph when its pair is inserted
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric="l2", max_degree=8, num_subspaces=4,
+                         ef_construction=60, seed=4)
+    ex = gix.export()
+    oix = orc.OracleIndex(ex["vectors"], ex["adj"], ex["a"], ex["c"], ex["e2"], ex["codes"], ex["rotation"],
+                          ex["codebooks"], ex["entry"], metric=ex["metric"])
+    codes, a, c, e2 = oix.recompute_edge_info()
+    zero = (ex["e2"] == 0) & (ex["adj"] != orc.EMPTY)
+    assert zero.sum() > 100                                 # duplicates do link to each other
+    assert np.array_equal(codes, ex["codes"])
+    assert np.allclose(a, ex["a"], rtol=2e-7, atol=0) and np.allclose(c, ex["c"], rtol=2e-7, atol=0)
+    assert np.all(ex["a"][zero] == 0) and np.all(ex["c"][zero] == 0)
+    q = (base[0:400:5] + 0.01 * rng.standard_normal((80, 32))).astype(np.float32)   # near duplicated points
+    gi, gd, _ = _assert_search_parity(gix, oix, q, 10, 64)
+    pair = gd[:, 0] == gd[:, 1]
+    assert pair.mean() >= 0.3 and np.array_equal(gi[pair, 0] + 1500, gi[pair, 1])    # a duplicated pair: smaller id first
+
+
 def test_cosine_and_ip(orc):
     PagIndex = _gpu()
     w = wl.workload(2, n=4000, nq=100)
