@@ -148,8 +148,9 @@ int pag_search(const pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uin
  * pag_insert (online insertion, Sec. 4.1): appends the m vectors X (dev,
  * float32 [m*d]); they receive ids n .. n+m-1 and are linked in shuffled
  * batches like the vectors of pag_build.  The vectors of one batch do not see
- * each other: a call whose vectors all lie in a region the index does not
- * cover yet links them better with a small pag_params.insert_subbatch.
+ * each other while they are linked; a batch found to crowd a region of its
+ * own (vectors inserted where the index has none yet) is therefore linked a
+ * second time once its vectors are part of the graph.
  * PAG_ECAPACITY if n + m exceeds pag_params.capacity.
  */
 int pag_insert(pag_index* ix, const float* X, uint64_t m);

@@ -166,7 +166,7 @@ __global__ void k_cand_segments(const u32* __restrict__ cand_cnt, u32 m, u32 can
 __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restrict__ recs,
                                                   pag_layout L, const u32* __restrict__ nodes, u32 m,
                                                   const u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
-                                                  const u64* __restrict__ pes,
+                                                  const u64* __restrict__ pes, float* __restrict__ e2,
                                                   u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sv = (float*)smem;                  // [2][d] candidate vectors
@@ -196,7 +196,8 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
         stage(vec, L.d, c1, sv, lane);
         stage(vec, L.d, c2, sv1, lane);
         __syncthreads();
-        bool occ1 = false, occ2 = !two;
+        // a node that is searched for a second time finds itself: never its own neighbour
+        bool occ1 = c1 == v, occ2 = !two || c2 == v;
         for (u32 s0 = 0; s0 < nk && !(occ1 && occ2); s0 += 4) {
             u32 sid[4];
             float d1[4], d2[4];
@@ -222,6 +223,8 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
     u32* ids = (u32*)(recs + (u64)v * L.rec_bytes);
     if ((u32)lane < L.deg) {
         ids[lane] = my_id;
+        // ||w - v||^2 as the search computed it: what the reverse-edge step reads should v be a target in the same batch
+        e2[(u64)v * L.deg + lane] = my_id == PAG_EMPTY ? 0.f : __uint_as_float(my_key);
         const u64 o = (u64)vi * L.deg + lane;
         rev_keys[o] = my_id == PAG_EMPTY ? PAG_KEY_INVALID : (((u64)my_id << 32) | my_key);
         rev_vals[o] = v;
@@ -234,7 +237,7 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
             u64 pk = PAG_KEY_INVALID;
             if (hk != PAG_KEY_INVALID) {
                 const u32 u = (u32)(hk & 0xFFFFFFFFull) >> 1;
-                bool dup = false;
+                bool dup = u == v;
                 for (u32 s = 0; s < nk; ++s) dup = dup || kept[s] == u;
                 if (!dup) pk = ((u64)u << 32) | 0x80000000ull | (hk >> 32);
             }
@@ -279,7 +282,7 @@ __global__ void __launch_bounds__(64) k_reverse(pag_vecs vec, uint8_t* __restric
         const bool from_pes = (k >> 31) & 1ull;
         const float duv = __uint_as_float((u32)(k & 0x7FFFFFFFull));
         const bool valid = (u32)lane < L.deg && id != PAG_EMPTY;
-        if (__ballot(valid && id == v)) continue;
+        if (v == u || __ballot(valid && id == v)) continue;
         // PES candidates are only added to available out-degree slots (Alg. 1, last loop)
         if (from_pes && __ballot((u32)lane < L.deg && id == PAG_EMPTY) == 0ull) continue;
         stage(vec, L.d, v, sv, lane);
@@ -346,16 +349,62 @@ __global__ void __launch_bounds__(64) k_reverse(pag_vecs vec, uint8_t* __restric
     }
 }
 
+// ---- is a batch a region of its own? ----
+// The nodes of a batch do not see each other.  For n_sample nodes of the batch, spread evenly over it, this counts
+// the batch-mates and the older nodes of the graph (n_probe of each, spread evenly) that lie closer than the
+// farthest neighbour the node has just been given: out[2i] mates, out[2i+1] older nodes.  In a batch drawn from
+// the same distribution as the graph the two fractions agree; where the batch-mates are many times denser (new
+// data inserted next to none of the old) the batch is linked a second time, now that its nodes are in the graph.
+// order: the ids being inserted, in insertion order; the first `done` of them and all ids below n_begin are in the
+// graph already, the batch is order[done .. done + m).
+__global__ void __launch_bounds__(64) k_batch_density(pag_vecs vec, const uint8_t* __restrict__ recs, const float* __restrict__ e2,
+                                                      pag_layout L, const u32* __restrict__ order, u64 n_begin, u64 done, u32 m,
+                                                      u32 n_sample, u32 n_probe, u32* __restrict__ out) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sv = (float*)smem;
+    const int lane = threadIdx.x;
+    const u32* nodes = order + done;
+    const u64 graph = n_begin + done;
+    const u32 x = nodes[(u64)blockIdx.x * m / n_sample];
+    stage(vec, L.d, x, sv, lane);
+    __syncthreads();
+    float far = 0.f;
+    if ((u32)lane < L.deg && ((const u32*)(recs + (u64)x * L.rec_bytes))[lane] != PAG_EMPTY) far = e2[(u64)x * L.deg + lane];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) far = fmaxf(far, __shfl_xor(far, o, 64));
+    u32 c_mate = 0, c_old = 0;
+    for (u32 j = 0; j < n_probe; j += 2) {
+        u32 y[4];
+        float dd[4];
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            const u32 jj = j + g < n_probe ? j + g : n_probe - 1;
+            y[g] = nodes[(u64)jj * m / n_probe];
+            const u64 t = (u64)jj * graph / n_probe;
+            y[2 + g] = t < n_begin ? (u32)t : order[t - n_begin];
+        }
+        dist_lds4(vec, L.d, sv, y, dd);
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            const bool in = j + g < n_probe;
+            c_mate += (in && y[g] != x && dd[g] < far) ? 1u : 0u;
+            c_old += (in && dd[2 + g] < far) ? 1u : 0u;
+        }
+    }
+    if (lane == 0) { out[2 * blockIdx.x] = c_mate; out[2 * blockIdx.x + 1] = c_old; }
+}
+
 struct BuildWs {
     u64* cand = nullptr; u64* cand_sorted = nullptr; u32* cand_cnt = nullptr; u64* pes = nullptr;
     u64 *rk_in = nullptr, *rk_out = nullptr; u32 *rv_in = nullptr, *rv_out = nullptr;
     u32* edges = nullptr; u32* n_edges = nullptr;
     u32* order = nullptr;
+    u32* density = nullptr;
     void* sort_tmp = nullptr; size_t sort_bytes = 0;
     int *seg_begin = nullptr, *seg_end = nullptr;
     void* seg_tmp = nullptr; size_t seg_bytes = 0;
     ~BuildWs() {
-        void* p[] = { cand, cand_sorted, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, order, sort_tmp, seg_begin, seg_end, seg_tmp };
+        void* p[] = { cand, cand_sorted, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, order, density, sort_tmp, seg_begin, seg_end, seg_tmp };
         for (void* x : p) if (x) (void)hipFree(x);
     }
 };
@@ -462,11 +511,12 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
             ix->ws_tab_cap = need;
         }
     }
-    while (done < count) {
-        const u64 graph = n_begin + done;                  // nodes in the graph so far
-        u64 m = std::min<u64>(count - done, max_batch);
-        m = std::min<u64>(m, std::max<u64>(1, graph / 2));
-        const u32* nodes = ws.order + done;
+    constexpr u32 kDensitySamples = 128, kDensityProbes = 2048;
+    constexpr double kCrowdedRatio = 4.0;
+    PAG_ALLOC(ws.density, kDensitySamples * 2 * 4);
+    // one linking pass over `m` listed nodes: search, RobustPrune, reverse edges, inference information
+    auto link = [&](const u32* nodes, u64 m) -> int {
+        int rc;
         // 1. the new nodes are their own queries (already rotated): rows gathered and widened to fp32, then their tables
         hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)m), dim3(64), 0, s, pag_vecs_of(ix), L.d, nodes, ix->ws_qrot);
         PAG_HIP(hipGetLastError());
@@ -494,7 +544,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         {
             const u32 plds = 2 * L.d * 4 + L.deg * 4;
             hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, nodes, (u32)m,
-                               ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ws.rk_in, ws.rv_in);
+                               ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ix->e2, ws.rk_in, ws.rv_in);
             PAG_HIP(hipGetLastError());
         }
         // 4. group reverse pairs by target
@@ -511,9 +561,35 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         u32 n_edges = 0;
         PAG_HIP(hipMemcpyAsync(&n_edges, ws.n_edges, 4, hipMemcpyDeviceToHost, s));
         PAG_HIP(hipStreamSynchronize(s));
-        if ((rc = pag_launch_edge_info_list(s, ix, ws.edges, n_edges))) return rc;
+        return pag_launch_edge_info_list(s, ix, ws.edges, n_edges);
+    };
+    while (done < count) {
+        const u64 graph = n_begin + done;                  // nodes in the graph so far
+        u64 m = std::min<u64>(count - done, max_batch);
+        m = std::min<u64>(m, std::max<u64>(1, graph / 2));
+        const u32* nodes = ws.order + done;
+        if ((rc = link(nodes, m))) return rc;
         done += m;
         ix->n_entry = (u32)std::min<u64>(entry_before + done, 1024);
+        // The nodes of the batch did not see each other.  Where they crowd a region of their own (sampled: around them
+        // batch-mates are several times denser, relative to the batch, than older nodes are relative to the graph), they
+        // are linked once more now that they are part of the graph.
+        if (m >= 64 && graph >= 64) {
+            const u32 ns = kDensitySamples, np = (u32)std::min<u64>(std::min<u64>(m, graph), kDensityProbes);
+            hipLaunchKernelGGL(k_batch_density, dim3(ns), dim3(64), L.d * 4, s, pag_vecs_of(ix), ix->rec, ix->e2, L, ws.order, n_begin,
+                               done - m, (u32)m, ns, np, ws.density);
+            PAG_HIP(hipGetLastError());
+            u32 h[kDensitySamples * 2];
+            PAG_HIP(hipMemcpyAsync(h, ws.density, sizeof h, hipMemcpyDeviceToHost, s));
+            PAG_HIP(hipStreamSynchronize(s));
+            double mates = 0.0, older = 0.0;
+            for (u32 i = 0; i < ns; ++i) { mates += h[2 * i]; older += h[2 * i + 1]; }
+            // both counts are out of ns * np probes: their ratio compares the two densities directly
+            const bool crowded = mates >= 32.0 && mates > kCrowdedRatio * std::max(older, 1.0);
+            if (crowded) {
+                if ((rc = link(nodes, m))) return rc;
+            }
+        }
     }
     PAG_HIP(hipStreamSynchronize(s));
     return PAG_OK;

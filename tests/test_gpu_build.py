@@ -330,3 +330,34 @@ def test_input_order_does_not_matter(orc):
         rec[name] = wl.recall_at_k(ids.cpu().numpy(), gt)
         gix.close()
     assert rec["random"] >= 0.9 and rec["sorted"] >= rec["random"] - 0.02, rec
+
+
+def test_inserting_a_region_the_index_does_not_cover(orc):
+    """pag_insert with vectors that all lie where the index has none yet (two whole clusters held out of the
+    build, then inserted with one call and, on a second index, 500 at a time in cluster order).  The vectors
+    of one batch do not see each other; the library notices that such a batch crowds a region of its own and
+    links it a second time.  Queries whose nearest neighbour is an inserted point must be answered about as
+    well as the others."""
+    PagIndex = _gpu()
+    w = wl.workload(3, n=40000, nq=3000)
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    lab = np.argmax(base @ base[:64].T, axis=1)
+    new = np.isin(lab, (3, 4))
+    old_rows = base[~new]
+    new_rows = base[new][np.argsort(lab[new], kind="stable")]
+    allv = np.concatenate([old_rows, new_rows])
+    assert 500 <= len(new_rows) <= 4000
+    gt, _ = wl.brute_force(allv, q, 10, w.metric)
+    near = gt[:, 0] >= len(old_rows)
+    assert near.sum() >= 30
+    ad, qd = torch.from_numpy(allv).cuda(), torch.from_numpy(q).cuda()
+    for step in (len(new_rows), 500):
+        gix = PagIndex.build(ad[:len(old_rows)].contiguous(), metric="ip", max_degree=w.deg, num_subspaces=w.P,
+                             ef_construction=200, seed=6, capacity=len(allv))
+        for i in range(len(old_rows), len(allv), step):
+            gix.insert(ad[i:i + step].contiguous())
+        ids, _ = gix.search(qd, 10, 96)
+        ids = ids.cpu().numpy()
+        r_near, r_else = wl.recall_at_k(ids[near], gt[near]), wl.recall_at_k(ids[~near], gt[~near])
+        gix.close()
+        assert r_else >= 0.9 and r_near >= r_else - 0.06, (step, r_near, r_else)
