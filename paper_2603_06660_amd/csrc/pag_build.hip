@@ -352,7 +352,7 @@ __global__ void __launch_bounds__(64) k_reverse(pag_vecs vec, uint8_t* __restric
 // ---- is a batch a region of its own? ----
 // The nodes of a batch do not see each other.  For n_sample nodes of the batch, spread evenly over it, this counts
 // the batch-mates and the older nodes of the graph (n_probe of each, spread evenly) that lie closer than the
-// farthest neighbour the node has just been given: out[2i] mates, out[2i+1] older nodes.  In a batch drawn from
+// farthest neighbour the node has just been given: added to out[2i] (mates) and out[2i+1] (older nodes).  In a batch drawn from
 // the same distribution as the graph the two fractions agree; where the batch-mates are many times denser (new
 // data inserted next to none of the old) the batch is linked a second time, now that its nodes are in the graph.
 // order: the ids being inserted, in insertion order; the first `done` of them and all ids below n_begin are in the
@@ -373,12 +373,15 @@ __global__ void __launch_bounds__(64) k_batch_density(pag_vecs vec, const uint8_
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) far = fmaxf(far, __shfl_xor(far, o, 64));
     u32 c_mate = 0, c_old = 0;
-    for (u32 j = 0; j < n_probe; j += 2) {
+    // the probes of one node are shared out over gridDim.y waves
+    const u32 per = (n_probe + gridDim.y - 1) / gridDim.y;
+    const u32 j0 = blockIdx.y * per, j1 = j0 + per < n_probe ? j0 + per : n_probe;
+    for (u32 j = j0; j < j1; j += 2) {
         u32 y[4];
         float dd[4];
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
-            const u32 jj = j + g < n_probe ? j + g : n_probe - 1;
+            const u32 jj = j + g < j1 ? j + g : j1 - 1;
             y[g] = nodes[(u64)jj * m / n_probe];
             const u64 t = (u64)jj * graph / n_probe;
             y[2 + g] = t < n_begin ? (u32)t : order[t - n_begin];
@@ -386,12 +389,12 @@ __global__ void __launch_bounds__(64) k_batch_density(pag_vecs vec, const uint8_
         dist_lds4(vec, L.d, sv, y, dd);
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
-            const bool in = j + g < n_probe;
+            const bool in = j + g < j1;
             c_mate += (in && y[g] != x && dd[g] < far) ? 1u : 0u;
             c_old += (in && dd[2 + g] < far) ? 1u : 0u;
         }
     }
-    if (lane == 0) { out[2 * blockIdx.x] = c_mate; out[2 * blockIdx.x + 1] = c_old; }
+    if (lane == 0) { atomicAdd(&out[2 * blockIdx.x], c_mate); atomicAdd(&out[2 * blockIdx.x + 1], c_old); }
 }
 
 struct BuildWs {
@@ -576,7 +579,8 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         // are linked once more now that they are part of the graph.
         if (m >= 64 && graph >= 64) {
             const u32 ns = kDensitySamples, np = (u32)std::min<u64>(std::min<u64>(m, graph), kDensityProbes);
-            hipLaunchKernelGGL(k_batch_density, dim3(ns), dim3(64), L.d * 4, s, pag_vecs_of(ix), ix->rec, ix->e2, L, ws.order, n_begin,
+            if ((rc = pag_launch_zero_u32(s, ws.density, 2 * ns))) return rc;
+            hipLaunchKernelGGL(k_batch_density, dim3(ns, 8), dim3(64), L.d * 4, s, pag_vecs_of(ix), ix->rec, ix->e2, L, ws.order, n_begin,
                                done - m, (u32)m, ns, np, ws.density);
             PAG_HIP(hipGetLastError());
             u32 h[kDensitySamples * 2];
