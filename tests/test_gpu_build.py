@@ -116,7 +116,7 @@ def test_build_is_deterministic(orc, cfg1_small, built):
 
 
 def test_online_insertion(orc, cfg1_small):
-    """Build on 2/3 of the data, insert the rest in two calls, search the whole set."""
+    """Build on 2/3 of the data, insert the rest in four calls (1, 3, 596 and 400 vectors), search the whole set."""
     PagIndex = _gpu()
     from paper_2603_06660_amd import PagError
     w, base, q, gt, gtk = cfg1_small
@@ -124,7 +124,9 @@ def test_online_insertion(orc, cfg1_small):
     bd = torch.from_numpy(base).cuda()
     gix = PagIndex.build(bd[:2000].contiguous(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
                          ef_construction=100, seed=22, capacity=n)
-    gix.insert(bd[2000:2600].contiguous())
+    gix.insert(bd[2000:2001].contiguous())                   # single vectors and a handful work too
+    gix.insert(bd[2001:2004].contiguous())
+    gix.insert(bd[2004:2600].contiguous())
     gix.insert(bd[2600:].contiguous())
     assert gix.describe()["n"] == n
     with pytest.raises(PagError):
@@ -361,3 +363,27 @@ def test_inserting_a_region_the_index_does_not_cover(orc):
         r_near, r_else = wl.recall_at_k(ids[near], gt[near]), wl.recall_at_k(ids[~near], gt[~near])
         gix.close()
         assert r_else >= 0.9 and r_near >= r_else - 0.06, (step, r_near, r_else)
+
+
+def test_index_grown_from_a_few_vectors(orc, cfg1_small):
+    """pag_build on one vector, then everything else through pag_insert: the entry list and the graph
+    grow with the insertions."""
+    PagIndex = _gpu()
+    w, base, q, gt, gtk = cfg1_small
+    n = base.shape[0]
+    bd = torch.from_numpy(base).cuda()
+    gix = PagIndex.build(bd[:1].contiguous(), metric="l2", max_degree=w.deg, num_subspaces=w.P,
+                         ef_construction=100, seed=23, capacity=n)
+    ids, dists = gix.search(torch.from_numpy(q).cuda(), 1, 10)
+    assert (ids.cpu().numpy() == 0).all()
+    for lo, hi in ((1, 2), (2, 40), (40, 700), (700, n)):
+        gix.insert(bd[lo:hi].contiguous())
+        assert gix.describe()["n"] == hi and gix.describe()["n_entry"] == min(hi, 1024)
+    ids, _ = gix.search(torch.from_numpy(q).cuda(), w.K, 64)
+    assert wl.recall_at_k(ids.cpu().numpy(), gt) >= 0.95
+    ex = gix.export()
+    _check_graph(orc, ex, n)
+    ent = ex["entry"]
+    assert len(set(ent.tolist())) == len(ent) == 1024 and ent.max() < n
+    oi, od, _ = _oracle_view(orc, ex).search(q, w.K, 64)
+    assert (ids.cpu().numpy() == oi).mean() >= 0.999
