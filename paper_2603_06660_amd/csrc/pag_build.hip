@@ -478,6 +478,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     if (done >= count) { PAG_HIP(hipStreamSynchronize(s)); return PAG_OK; }
 
     u64 max_batch = ix->subbatch ? ix->subbatch : std::min<u64>(16384, std::max<u64>(1024, n_end / 50));
+    max_batch = std::min<u64>(max_batch, count);       // a small insertion gets small workspaces
     PAG_ALLOC(ws.cand, max_batch * cand_cap * 8);
     PAG_ALLOC(ws.cand_sorted, max_batch * cand_cap * 8);
     PAG_ALLOC(ws.cand_cnt, max_batch * 4);
