@@ -23,13 +23,18 @@
  *   the per-hop estimate is evaluated in fp32 as fmaf(-2 a_i, S_i, D_u + c_i)
  *   with S_i summed over the subspaces in increasing order.
  *
- * Parity pins: see tests/test_oracle_*.py.  Two parts are "parity unpinned":
- * which traversal the heuristic takes with the projection test active (the
- * hop-synchronous reading below *is* the definition; what is pinned are runs
- * traced by hand -- the round mechanics with the test switched off, the same
- * with the test on where its estimate is exact (collinear points), and one hop
- * of a hand-computed general case), and the graph the sequential build
- * produces (validated only through recall against brute force).
+ * Parity pins: see tests/test_oracle_*.py.  One part is "parity unpinned":
+ * which traversal the heuristic takes with the projection test active on
+ * general data (the hop-synchronous reading below *is* the definition; what is
+ * pinned are runs traced by hand -- the round mechanics with the test switched
+ * off, the same with the test on where its estimate is exact (collinear
+ * points, including an exact tie with the threshold), and one hop of a
+ * hand-computed general case).  The pieces of Alg. 1 are pinned by hand-made
+ * planar cases: the initial nodes, every branch of the reverse-edge rule, the
+ * PES screening and the trimming of H(v) inside the search, the verification
+ * of a buffered candidate, and one whole insertion traced by hand; the
+ * batch-synchronous construction is pinned to the sequential one (batches of
+ * one node give the same graph).
  */
 #include <math.h>
 #include <stdint.h>
@@ -562,16 +567,6 @@ void orc_reverse_edge(orc_index *ix, uint32_t u, uint32_t v, float duv) {
 }
 
 /*
- * Sequential construction, Step 1 of the indexing phase (Alg. 1 without the PES
- * buffer): nodes [n_start, n_end) are inserted one after another into the graph
- * that already holds nodes [0, n_start).  ix->vec must already hold the rotated
- * vectors of all nodes; adjacency arrays of the new nodes must be ORC_EMPTY.
- * With n_start == 0 the first min(efC, 100) nodes are linked to their nearest
- * min(deg, .) among themselves ("select b initial nodes, connect them").
- * use_pes: Step 2 and Step 3 as well -- every insertion fills its buffer H(v) (capacity deg =
- * 2M) through the PES screening, and after all insertions the buffered candidates are verified.
- */
-/*
  * Verification of one PES candidate u -> v (Alg. 1, last loop): the RobustPrune condition of
  * Eq. 1 is evaluated exactly; an accepted edge is added only to a free out-degree slot of u,
  * existing edges are kept unchanged.  Returns 1 if the edge was added.
@@ -580,6 +575,7 @@ int orc_pes_edge(orc_index *ix, uint32_t u, uint32_t v, float duv) {
     const uint32_t d = ix->d, deg = ix->deg;
     const float *vv = ix->vec + (uint64_t)v * d;
     int free_slot = -1;
+    if (u == v) return 0;
     for (uint32_t i = 0; i < deg; ++i) {
         uint64_t s = (uint64_t)u * deg + i;
         uint32_t w = ix->adj[s];
@@ -597,8 +593,68 @@ int orc_pes_edge(orc_index *ix, uint32_t u, uint32_t v, float duv) {
     return 1;
 }
 
+/*
+ * The search of Alg. 1 for one point v (already rotated) over the nodes [0, n_nodes): Alg. 2's
+ * loop with ef = efC, b = min(efC, 100) and R_L of capacity efC, plus the PES screening of every
+ * expanded node.  Outputs R_L (ascending by (dist, id)) and the buffer H(v) (capacity deg = 2M,
+ * ascending).  Exposed so that tests can look at the two lists themselves.
+ */
+int orc_index_search(const orc_index *ix, uint64_t n_nodes, const float *v, uint32_t efC,
+                     uint32_t *cand_ids, float *cand_keys, uint32_t *n_cand,
+                     uint32_t *pes_ids, float *pes_keys, uint32_t *n_pes, orc_counters *ctr) {
+    const uint32_t d = ix->d, P = ix->P, deg = ix->deg;
+    uint32_t b = efC < 100 ? efC : 100;
+    if (b == 0 || d % P != 0) return -1;
+    orc_counters local;
+    memset(&local, 0, sizeof local);
+    orc_scratch sc = { (uint8_t *)calloc(ix->n ? ix->n : 1, 1), NULL, 0, 0 };
+    float *T = (float *)malloc(sizeof(float) * P * ORC_M);
+    ent *rl = (ent *)malloc(sizeof(ent) * ((size_t)efC + b));
+    ent *H = (ent *)malloc(sizeof(ent) * deg);
+    uint32_t n_out = 0, nH = 0;
+    orc_table(d, P, ix->cb, v, T, NULL);
+    orc_search_core(ix, n_nodes, v, T, efC, b, efC, 0, &sc, rl, &n_out, &local, H, &nH, deg);
+    for (uint32_t i = 0; i < n_out; ++i) { cand_ids[i] = rl[i].id; cand_keys[i] = rl[i].dist; }
+    *n_cand = n_out;
+    for (uint32_t i = 0; i < nH; ++i) { pes_ids[i] = H[i].id; pes_keys[i] = H[i].dist; }
+    *n_pes = nH;
+    if (ctr) *ctr = local;
+    free(sc.seen); free(sc.seen_list); free(T); free(rl); free(H);
+    return 0;
+}
+
+/* the first n_init nodes are linked to their nearest min(deg, n_init - 1) peers, ascending by (dist, id)
+ * (Alg. 1: the initial nodes are selected and connected) */
+static void init_nodes(orc_index *ix, uint64_t n_init) {
+    const uint32_t d = ix->d, deg = ix->deg;
+    ent *tmp = (ent *)malloc(sizeof(ent) * (n_init ? n_init : 1));
+    for (uint64_t v = 0; v < n_init; ++v) {
+        uint32_t m = 0;
+        for (uint64_t o = 0; o < n_init; ++o) {
+            if (o == v) continue;
+            tmp[m].dist = orc_key(d, ix->vec + v * d, ix->vec + o * d);
+            tmp[m].id = (uint32_t)o; tmp[m].visited = 0; m++;
+        }
+        qsort(tmp, m, sizeof(ent), ent_cmp);
+        for (uint32_t i = 0; i < m && i < deg; ++i) write_edge(ix, (uint32_t)v, i, tmp[i].id);
+    }
+    free(tmp);
+}
+
+/*
+ * Sequential construction (Alg. 1): nodes [n_start, n_end) are inserted one after another into
+ * the graph that already holds nodes [0, n_start).  ix->vec must already hold the rotated
+ * vectors of all nodes; adjacency arrays of the new nodes must be ORC_EMPTY.
+ * With n_start == 0 the first min(efC, 100) nodes are the initial nodes: each is linked to its
+ * nearest min(deg, .) among them.
+ * Step 1 per node: search, RobustPrune -> N_out(v), reverse edges, inference information.
+ * use_pes: Step 2 and Step 3 as well -- every insertion fills its buffer H(v) (capacity deg = 2M)
+ * through the PES screening; the buffered candidates are verified after all insertions
+ * (pes_every == 0, Alg. 1's last loop) or after every pes_every insertions (Sec. 4.2, online
+ * insertion: the refinement runs after an insertion batch), in insertion order.
+ */
 int orc_build(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, orc_counters *ctr, int use_pes,
-              uint64_t *pes_added) {
+              uint64_t pes_every, uint64_t *pes_added) {
     const uint32_t d = ix->d, P = ix->P, deg = ix->deg;
     uint32_t b = efC < 100 ? efC : 100;
     if (b == 0 || d % P != 0) return -1;
@@ -611,25 +667,16 @@ int orc_build(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, orc
     float *ckey = (float *)malloc(sizeof(float) * ((size_t)efC + b));
     uint32_t *kept = (uint32_t *)malloc(sizeof(uint32_t) * deg);
     float *kkey = (float *)malloc(sizeof(float) * deg);
-    ent *Hall = use_pes ? (ent *)malloc(sizeof(ent) * (size_t)(n_end - n_start) * deg) : NULL;
-    uint32_t *nHall = use_pes ? (uint32_t *)calloc(n_end - n_start, sizeof(uint32_t)) : NULL;
+    const uint64_t count = n_end > n_start ? n_end - n_start : 0;
+    ent *Hall = use_pes ? (ent *)malloc(sizeof(ent) * (size_t)(count ? count : 1) * deg) : NULL;
+    uint32_t *nHall = use_pes ? (uint32_t *)calloc(count ? count : 1, sizeof(uint32_t)) : NULL;
     uint64_t v0 = n_start;
     if (n_start == 0) {
         uint64_t n_init = n_end < b ? n_end : b;
-        ent *tmp = (ent *)malloc(sizeof(ent) * (n_init ? n_init : 1));
-        for (uint64_t v = 0; v < n_init; ++v) {
-            uint32_t m = 0;
-            for (uint64_t o = 0; o < n_init; ++o) {
-                if (o == v) continue;
-                tmp[m].dist = orc_key(d, ix->vec + v * d, ix->vec + o * d);
-                tmp[m].id = (uint32_t)o; tmp[m].visited = 0; m++;
-            }
-            qsort(tmp, m, sizeof(ent), ent_cmp);
-            for (uint32_t i = 0; i < m && i < deg; ++i) write_edge(ix, (uint32_t)v, i, tmp[i].id);
-        }
-        free(tmp);
+        init_nodes(ix, n_init);
         v0 = n_init;
     }
+    uint64_t added = 0, verified = v0;     /* buffers of nodes [verified, v] are pending */
     for (uint64_t v = v0; v < n_end; ++v) {
         const float *vv = ix->vec + v * d;
         orc_table(d, P, ix->cb, vv, T, NULL);
@@ -641,18 +688,123 @@ int orc_build(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, orc
         uint32_t nk = orc_robust_prune(ix, n_out, cand, ckey, deg, kept, kkey);
         for (uint32_t i = 0; i < nk; ++i) write_edge(ix, (uint32_t)v, i, kept[i]);
         for (uint32_t i = 0; i < nk; ++i) orc_reverse_edge(ix, kept[i], (uint32_t)v, kkey[i]);
-    }
-    uint64_t added = 0;
-    if (use_pes)
-        for (uint64_t v = v0; v < n_end; ++v) {
-            const ent *H = Hall + (v - n_start) * deg;
-            for (uint32_t i = 0; i < nHall[v - n_start]; ++i)
-                added += (uint64_t)orc_pes_edge(ix, H[i].id, (uint32_t)v, H[i].dist);
+        const int flush = use_pes && (v + 1 == n_end || (pes_every && (v + 1 - v0) % pes_every == 0));
+        if (flush) {
+            for (uint64_t x = verified; x <= v; ++x) {
+                const ent *Hx = Hall + (x - n_start) * deg;
+                for (uint32_t i = 0; i < nHall[x - n_start]; ++i)
+                    added += (uint64_t)orc_pes_edge(ix, Hx[i].id, (uint32_t)x, Hx[i].dist);
+            }
+            verified = v + 1;
         }
+    }
     if (pes_added) *pes_added = added;
     if (ctr) *ctr = local;
     free(Hall); free(nHall);
     free(sc.seen); free(sc.seen_list); free(T); free(rl); free(cand); free(ckey); free(kept); free(kkey);
+    return 0;
+}
+
+/*
+ * Batch-synchronous construction: the reading of Alg. 1 for many insertions at once (the paper
+ * builds with many threads and does not say in which order their updates land).  Nodes are taken
+ * in id order in batches of m = min(remaining, max_batch, max(1, nodes in the graph / 2)).  The
+ * nodes of a batch all search the graph as it was before the batch (they do not see each other);
+ * then every one gets its N_out by RobustPrune; then the reverse edges and the buffered PES
+ * candidates of the whole batch are applied target by target, for each target first the reverse
+ * edges, then the PES candidates, each group ascending by distance (ties: by position of the
+ * source in the batch, then by its slot).  With max_batch == 1 this is the sequential
+ * construction with the PES buffers verified after every insertion.
+ */
+typedef struct { uint32_t target, pes, src; float dist; uint64_t seq; } rev_pair;
+
+static int pair_cmp(const void *px, const void *py) {
+    const rev_pair *x = (const rev_pair *)px, *y = (const rev_pair *)py;
+    if (x->target != y->target) return x->target < y->target ? -1 : 1;
+    if (x->pes != y->pes) return x->pes < y->pes ? -1 : 1;
+    if (x->dist != y->dist) return x->dist < y->dist ? -1 : 1;
+    if (x->seq != y->seq) return x->seq < y->seq ? -1 : 1;
+    return 0;
+}
+
+int orc_build_batched(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, uint64_t max_batch,
+                      int use_pes, orc_counters *ctr, uint64_t *pes_added, uint64_t *n_batches) {
+    const uint32_t d = ix->d, P = ix->P, deg = ix->deg;
+    uint32_t b = efC < 100 ? efC : 100;
+    if (b == 0 || d % P != 0 || max_batch == 0) return -1;
+    orc_counters local;
+    memset(&local, 0, sizeof local);
+    orc_scratch sc = { (uint8_t *)calloc(n_end ? n_end : 1, 1), NULL, 0, 0 };
+    float *T = (float *)malloc(sizeof(float) * P * ORC_M);
+    const size_t rl_room = (size_t)efC + b;
+    ent *rl = (ent *)malloc(sizeof(ent) * rl_room * max_batch);      /* R_L of every node of the batch */
+    uint32_t *n_rl = (uint32_t *)malloc(sizeof(uint32_t) * max_batch);
+    ent *Hb = (ent *)malloc(sizeof(ent) * (size_t)deg * max_batch);  /* H(v) of every node of the batch */
+    uint32_t *nHb = (uint32_t *)malloc(sizeof(uint32_t) * max_batch);
+    uint32_t *cand = (uint32_t *)malloc(sizeof(uint32_t) * rl_room);
+    float *ckey = (float *)malloc(sizeof(float) * rl_room);
+    uint32_t *kept = (uint32_t *)malloc(sizeof(uint32_t) * deg);
+    float *kkey = (float *)malloc(sizeof(float) * deg);
+    rev_pair *pairs = (rev_pair *)malloc(sizeof(rev_pair) * 2 * (size_t)deg * max_batch);
+    uint64_t v0 = n_start, added = 0, batches = 0;
+    if (n_start == 0) {
+        uint64_t n_init = n_end < b ? n_end : b;
+        init_nodes(ix, n_init);
+        v0 = n_init;
+    }
+    while (v0 < n_end) {
+        const uint64_t graph = v0;                       /* ids below v0 are in the graph */
+        uint64_t m = n_end - v0;
+        if (m > max_batch) m = max_batch;
+        const uint64_t half = graph / 2 ? graph / 2 : 1;
+        if (m > half) m = half;
+        /* 1. every node of the batch searches the graph of before the batch */
+        for (uint64_t j = 0; j < m; ++j) {
+            const float *vv = ix->vec + (v0 + j) * d;
+            orc_table(d, P, ix->cb, vv, T, NULL);
+            nHb[j] = 0;
+            orc_search_core(ix, graph, vv, T, efC, b, efC, 0, &sc, rl + j * rl_room, &n_rl[j], &local,
+                            use_pes ? Hb + j * deg : NULL, use_pes ? &nHb[j] : NULL, deg);
+        }
+        /* 2. RobustPrune -> N_out(v); the reverse edges and PES candidates are collected */
+        uint64_t np = 0;
+        for (int pes = 0; pes <= (use_pes ? 1 : 0); ++pes)
+            for (uint64_t j = 0; j < m; ++j) {
+                const uint32_t v = (uint32_t)(v0 + j);
+                if (!pes) {
+                    const ent *r = rl + j * rl_room;
+                    for (uint32_t i = 0; i < n_rl[j]; ++i) { cand[i] = r[i].id; ckey[i] = r[i].dist; }
+                    uint32_t nk = orc_robust_prune(ix, n_rl[j], cand, ckey, deg, kept, kkey);
+                    for (uint32_t i = 0; i < nk; ++i) {
+                        write_edge(ix, v, i, kept[i]);
+                        rev_pair p = { kept[i], 0, v, kkey[i], np };
+                        pairs[np++] = p;
+                    }
+                } else {
+                    for (uint32_t i = 0; i < nHb[j]; ++i) {
+                        const ent h = Hb[j * deg + i];
+                        int dup = h.id == v;             /* already an out-neighbour of v: it has its reverse edge */
+                        for (uint32_t s = 0; s < deg; ++s) if (ix->adj[(uint64_t)v * deg + s] == h.id) dup = 1;
+                        if (dup) continue;
+                        rev_pair p = { h.id, 1, v, h.dist, np };
+                        pairs[np++] = p;
+                    }
+                }
+            }
+        /* 3. applied target by target */
+        qsort(pairs, np, sizeof(rev_pair), pair_cmp);
+        for (uint64_t i = 0; i < np; ++i) {
+            if (pairs[i].pes) added += (uint64_t)orc_pes_edge(ix, pairs[i].target, pairs[i].src, pairs[i].dist);
+            else orc_reverse_edge(ix, pairs[i].target, pairs[i].src, pairs[i].dist);
+        }
+        v0 += m;
+        batches++;
+    }
+    if (pes_added) *pes_added = added;
+    if (n_batches) *n_batches = batches;
+    if (ctr) *ctr = local;
+    free(sc.seen); free(sc.seen_list); free(T); free(rl); free(n_rl); free(Hb); free(nHb);
+    free(cand); free(ckey); free(kept); free(kkey); free(pairs);
     return 0;
 }
 

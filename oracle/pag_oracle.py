@@ -66,6 +66,7 @@ def lib():
         _lib.orc_est32.restype = C.c_float
         _lib.orc_est32.argtypes = [C.c_float] * 4
         _lib.orc_robust_prune.restype = C.c_uint32
+        _lib.orc_pes_edge.restype = C.c_int
     return _lib
 
 
@@ -208,15 +209,11 @@ class OracleIndex:
                       _p(self.codes), _p(self.rot), _p(self.cb), _p(self.entry))
 
     # -- construction ---------------------------------------------------
-    @classmethod
-    def build(cls, data, metric=L2, deg=32, P=16, efC=100, seed=1, rot=None, cb=None, pes=True, vec_f16=False):
-        """Alg. 1 sequentially over `data` (raw float32 [n, d]); pes=False leaves out Steps 2 and 3.
-        vec_f16: the rotated vectors are rounded to 16-bit floats (the paper's payload, Sec. 4.2) and the
-        index is built over those values."""
+    @staticmethod
+    def _ingest(data, metric, rot, vec_f16):
+        """Rows of `data` normalised (COS), rotated by Q and, with vec_f16, rounded to 16-bit floats."""
         data = _f32(data)
         n, d = data.shape
-        rot = make_transform(d, seed) if rot is None else _f32(rot)
-        cb = make_codebooks(d, P, seed) if cb is None else _f32(cb)
         vec = np.empty_like(data)
         tmp = np.empty(d, dtype=np.float32)
         L = lib()
@@ -228,19 +225,89 @@ class OracleIndex:
             L.orc_rotate(C.c_uint32(d), _p(rot), _p(x), _p(vec[i]))
         if vec_f16:
             vec = vec.astype(np.float16).astype(np.float32)
+        return vec
+
+    def _link(self, n_start, efC, pes, pes_every, max_batch):
+        """Alg. 1 over the nodes [n_start, n): sequential (max_batch = 0) or batch-synchronous."""
+        L = lib()
+        ctr = Counters()
+        st = self._struct()
+        added = C.c_uint64(0)
+        batches = C.c_uint64(0)
+        if max_batch:
+            rc = L.orc_build_batched(C.byref(st), C.c_uint32(efC), C.c_uint64(n_start), C.c_uint64(self.n),
+                                     C.c_uint64(max_batch), C.c_int(1 if pes else 0), C.byref(ctr),
+                                     C.byref(added), C.byref(batches))
+        else:
+            rc = L.orc_build(C.byref(st), C.c_uint32(efC), C.c_uint64(n_start), C.c_uint64(self.n), C.byref(ctr),
+                             C.c_int(1 if pes else 0), C.c_uint64(pes_every), C.byref(added))
+        assert rc == 0
+        self.build_counters = ctr.as_dict()
+        self.pes_edges_added = int(added.value)
+        self.batches = int(batches.value)
+
+    @classmethod
+    def build(cls, data, metric=L2, deg=32, P=16, efC=100, seed=1, rot=None, cb=None, pes=True, vec_f16=False,
+              pes_every=0, max_batch=0):
+        """Alg. 1 over `data` (raw float32 [n, d]) in row order; pes=False leaves out Steps 2 and 3.
+        pes_every: the PES buffers are verified after every so many insertions (0: after the last one).
+        max_batch: 0 = one node after another; otherwise the batch-synchronous construction with batches
+        of at most that many nodes.
+        vec_f16: the rotated vectors are rounded to 16-bit floats (the paper's payload, Sec. 4.2) and the
+        index is built over those values."""
+        data = _f32(data)
+        n, d = data.shape
+        rot = make_transform(d, seed) if rot is None else _f32(rot)
+        cb = make_codebooks(d, P, seed) if cb is None else _f32(cb)
+        vec = cls._ingest(data, metric, rot, vec_f16)
         self = cls(vec, np.full((n, deg), EMPTY, np.uint32), np.zeros((n, deg), np.float32),
                    np.zeros((n, deg), np.float32), np.zeros((n, deg), np.float32),
                    np.zeros((n, deg, P), np.uint8), rot, cb,
                    np.arange(min(n, 1024), dtype=np.uint32), metric)
+        self._link(0, efC, pes, pes_every, max_batch)
+        return self
+
+    def insert(self, data, efC=100, pes=True, pes_every=0, max_batch=0, vec_f16=False):
+        """Online insertion (Sec. 4.1): the rows of `data` are appended and linked like the nodes of build();
+        the entry list grows with them until it holds 1024 nodes."""
+        new = self._ingest(data, self.metric, self.rot, vec_f16)
+        m, n0 = new.shape[0], self.n
+        self.vec = np.ascontiguousarray(np.concatenate([self.vec, new]))
+        self.adj = np.ascontiguousarray(np.concatenate([self.adj, np.full((m, self.deg), EMPTY, np.uint32)]))
+        for k in ("a", "c", "e2"):
+            setattr(self, k, np.ascontiguousarray(np.concatenate([getattr(self, k), np.zeros((m, self.deg), np.float32)])))
+        self.codes = np.ascontiguousarray(np.concatenate([self.codes, np.zeros((m, self.deg, self.P), np.uint8)]))
+        self.n = n0 + m
+        if self.entry.size < 1024:
+            grow = np.arange(n0, min(self.n, n0 + 1024 - self.entry.size), dtype=np.uint32)
+            self.entry = np.ascontiguousarray(np.concatenate([self.entry, grow]))
+        self._link(n0, efC, pes, pes_every, max_batch)
+
+    def index_search(self, v_rot, efC, n_nodes=None):
+        """The search of one insertion (Alg. 1) for the rotated point v over the nodes [0, n_nodes):
+        -> (R_L ids, R_L keys, H(v) ids, H(v) keys, counters)."""
+        v_rot = _f32(v_rot)
+        room = efC + min(efC, 100)
+        ci, ck = np.empty(room, np.uint32), np.empty(room, np.float32)
+        hi, hk = np.empty(self.deg, np.uint32), np.empty(self.deg, np.float32)
+        nc, nh = C.c_uint32(0), C.c_uint32(0)
         ctr = Counters()
         st = self._struct()
-        added = C.c_uint64(0)
-        rc = L.orc_build(C.byref(st), C.c_uint32(efC), C.c_uint64(0), C.c_uint64(n), C.byref(ctr),
-                         C.c_int(1 if pes else 0), C.byref(added))
+        rc = lib().orc_index_search(C.byref(st), C.c_uint64(self.n if n_nodes is None else n_nodes), _p(v_rot),
+                                    C.c_uint32(efC), _p(ci), _p(ck), C.byref(nc), _p(hi), _p(hk), C.byref(nh),
+                                    C.byref(ctr))
         assert rc == 0
-        self.build_counters = ctr.as_dict()
-        self.pes_edges_added = int(added.value)
-        return self
+        return ci[:nc.value].copy(), ck[:nc.value].copy(), hi[:nh.value].copy(), hk[:nh.value].copy(), ctr.as_dict()
+
+    def reverse_edge(self, u, v, duv):
+        """The reverse edge u -> v of an insertion (Sec. 2.1; Eq. 1), applied in place."""
+        st = self._struct()
+        lib().orc_reverse_edge(C.byref(st), C.c_uint32(u), C.c_uint32(v), C.c_float(duv))
+
+    def pes_edge(self, u, v, duv):
+        """Verification of the PES candidate u -> v (Alg. 1, last loop), applied in place; -> 1 if added."""
+        st = self._struct()
+        return int(lib().orc_pes_edge(C.byref(st), C.c_uint32(u), C.c_uint32(v), C.c_float(duv)))
 
     # -- search ---------------------------------------------------------
     def search(self, Q, K, efS, b=0, flags=0, threads=1, want_seen=False):

@@ -260,7 +260,8 @@ def _read_hand_trace():
 def test_hand_traced_tfb_rounds(orc):
     """Alg. 2's round mechanics (eviction to R_T, false positives to R_F, FIFO overflow, refill of W with
     visited flags kept, termination) against traces worked out by hand: tests/golden/tfb_hand_trace.txt.
-    Two of the traces run with the routing test on, on a geometry where its estimate is exact."""
+    Four of the traces run with the routing test on, on a geometry where its estimate is exact; the last
+    one is an exact tie between an estimate and the threshold (Eq. 3 asks for a positive value)."""
     common, cases = _read_hand_trace()
     b, K = int(common["b"]), int(common["K"])
     deg, P = 2, 1
@@ -269,7 +270,7 @@ def test_hand_traced_tfb_rounds(orc):
     axis[0, 1] = [-1, 0]
     axis[0, 2] = [0, 1]
     axis[0, 3] = [0, -1]
-    assert len(cases) == 5 and sum(c.get("prt") == "on" for c in cases) == 3
+    assert len(cases) == 6 and sum(c.get("prt") == "on" for c in cases) == 4
     for case in cases:
         pos = np.array(case.get("positions", common["positions"]).split(), dtype=np.float32)
         n = len(pos)
