@@ -61,7 +61,8 @@ typedef struct {
     uint32_t num_subspaces;   /* [L] number of subspaces of the rotated space; 16 projection vectors each */
     uint32_t ef_construction; /* [efC] nodes visited per insertion; W has min(efC, 100) nodes while indexing */
     uint32_t search_b;        /* working-set size b = |W| when searching; 0 = max(10, K) (Alg. 2) */
-    uint32_t insert_subbatch; /* vectors inserted concurrently per step of the batch-synchronous build; 0 = auto */
+    uint32_t insert_subbatch; /* vectors inserted concurrently per step of the batch-synchronous build; 0 = auto;
+                                 at most 2^20 */
     uint32_t flags;           /* PAG_FLAG_* */
     uint64_t capacity;        /* maximum number of vectors including later pag_insert calls; 0 = n */
     uint64_t seed;            /* seed of the random transform Q and of the codebooks */
@@ -73,6 +74,14 @@ typedef struct {
                                    bytes per exact distance; the index then *is* the rounded data, and all arithmetic on it
                                    stays fp32/fp64.  Needs d % 8 == 0.  Build / import time only. */
 #define PAG_FLAG_NO_PES 2u    /* ablation: index without the PES candidate buffers H(v) (Eq. 5; Alg. 1's last loop) */
+#define PAG_FLAG_KEEP_ORDER 8u /* build / insert link the vectors in the order given (row 0 first) instead of a
+                                  seeded shuffle: for input that is already in random order.  With
+                                  insert_subbatch = 1 this is Alg. 1 as printed, one node after another, the
+                                  PES buffer of a node verified right after its insertion. */
+#define PAG_FLAG_EXACT_TEST_COUNT 16u /* diagnostic, search time: long searches resolve the seen set for every
+                                  neighbour before the projection test instead of only for those that pass it,
+                                  so that pag_counters.tests counts exactly the unseen neighbours (Sec. 4.2's
+                                  gamma = passes / tests).  Results are unchanged; the search is a few % slower. */
 
 /*
  * Flat host view of an index (Alg. 1 output: node set, edge set E, inference
@@ -107,7 +116,8 @@ typedef struct {
     uint64_t hops;               /* expanded nodes (n' of Sec. 4.2) */
     uint64_t tests;              /* neighbours the projection test was evaluated for: the unseen ones; in long
                                     searches also already-seen ones that only the second level of the seen
-                                    set would have recognised (it is consulted for passing neighbours only) */
+                                    set would have recognised (it is consulted for passing neighbours only),
+                                    unless PAG_FLAG_EXACT_TEST_COUNT is set */
     uint64_t passes;             /* of those, how many passed (gamma = passes / tests) */
     uint64_t exact;              /* exact distances computed, entry nodes included */
     uint64_t rounds;             /* TFB rounds */
@@ -119,6 +129,8 @@ typedef struct {
     double   last_build_ms;         /* wall time of the last pag_build / pag_insert */
     uint64_t phase_cycles[6];       /* diagnostic: per-phase clock ticks of the search kernel, summed over waves;
                                        all zero unless the library was compiled with -DPAG_PHASE_TIMERS */
+    uint64_t relinked_batches;      /* insertion batches, since the index was created, that were found to crowd a
+                                       region of their own and were linked a second time (see pag_insert) */
 } pag_counters;
 
 /*
@@ -152,6 +164,10 @@ int pag_search(const pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uin
  * own (vectors inserted where the index has none yet) is therefore linked a
  * second time once its vectors are part of the graph.
  * PAG_ECAPACITY if n + m exceeds pag_params.capacity.
+ * If the call fails half way (a HIP error, memory), the index keeps answering
+ * searches over the n vectors it had, but some of their out-edges may already
+ * point at the vectors that were being added: further pag_insert calls on it
+ * are refused with PAG_EINVAL.
  */
 int pag_insert(pag_index* ix, const float* X, uint64_t m);
 
@@ -170,7 +186,8 @@ int pag_import(const pag_arrays* in, const pag_params* params, pag_index** out);
 /* Statistics summed over all searches since the last reset (set out->struct_size first), and the reset. */
 int pag_get_counters(const pag_index* ix, pag_counters* out);
 int pag_reset_counters(pag_index* ix);
-/* Changes search-time settings of an existing index: working-set size (0 = max(10,K)) and PAG_FLAG_* bits. */
+/* Changes search-time settings of an existing index: working-set size (0 = max(10,K)) and the search-time
+ * PAG_FLAG_* bits (PAG_FLAG_NO_PRT, PAG_FLAG_EXACT_TEST_COUNT); the bits fixed at build time stay. */
 int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t flags);
 /* log2 of the slots of the per-query LDS seen-set table; 0 = choose from efS.  Small values exercise the HBM spill path. */
 int pag_set_seen_capacity_log2(pag_index* ix, uint32_t log2_slots);
@@ -178,10 +195,10 @@ int pag_set_seen_capacity_log2(pag_index* ix, uint32_t log2_slots);
 /*
  * Single steps of the search, exposed for kernel-level parity checks.
  *
- * pag_prepare_queries (Alg. 2, "q <- Qq" and "build a projection table"):
+ * pag_prepare_queries (Alg. 2, rotation step and projection-table step):
  *   q_rot (dev float32 [nq*d]) and tables (dev float32 [nq*P*16],
  *   tables[i][l][j] = <q_l, r_jl>) of the queries Q (dev).
- * pag_exact_distances (Alg. 2, "compute the distance between q and w"):
+ * pag_exact_distances (Alg. 2, exact-distance step):
  *   keys[i*m+j] = ||q_rot[i] - x[ids[i*m+j]]||^2 for already rotated queries;
  *   ids dev uint32 [nq*m] (each < n), keys dev float32 [nq*m].
  * pag_screen (Eq. 3 + Eq. 4 in estimate form): for query i expanding node
@@ -191,6 +208,14 @@ int pag_set_seen_capacity_log2(pag_index* ix, uint32_t log2_slots);
  * pag_edge_info (Sec. 3.1 / Appendix B): recomputes codes, a, c, e2 of every
  *   stored edge of nodes [node_begin, node_end) from the vectors; outputs are
  *   host arrays [(node_end-node_begin)*deg (*P)].
+ * pag_insertion_candidates (Alg. 1, the search of one insertion; Eq. 5): what
+ *   inserting each of the m vectors X (dev, float32 [m*d], raw like the input of
+ *   pag_insert) into the index as it stands would start from, without changing
+ *   the index: the list R_L (capacity efC, ascending by (dist, id)) and the PES
+ *   buffer H(v) (capacity max_degree, ascending).  Outputs are host arrays:
+ *   cand_ids / cand_keys [m*efC] with cand_count [m] valid entries per vector,
+ *   pes_ids / pes_keys [m*max_degree] with pes_count [m]; keys are squared
+ *   distances.  With PAG_FLAG_NO_PES the buffers come back empty.
  */
 int pag_prepare_queries(const pag_index* ix, const float* Q, uint64_t nq, float* q_rot, float* tables);
 int pag_exact_distances(const pag_index* ix, const float* q_rot, uint64_t nq, const uint32_t* ids,
@@ -199,6 +224,9 @@ int pag_screen(const pag_index* ix, const float* tables, uint64_t nq, const uint
                const float* Du, float* est);
 int pag_edge_info(const pag_index* ix, uint64_t node_begin, uint64_t node_end, uint8_t* codes,
                   float* a, float* c, float* e2);
+int pag_insertion_candidates(const pag_index* ix, const float* X, uint64_t m, uint32_t* cand_ids,
+                             float* cand_keys, uint32_t* cand_count, uint32_t* pes_ids, float* pes_keys,
+                             uint32_t* pes_count);
 
 /*
  * Diagnostic for the roofline (no step of the method): reads `rows` whole rows of the index's vector

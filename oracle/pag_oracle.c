@@ -79,12 +79,12 @@ double orc_sqdist64(uint32_t d, const float *x, const float *y) {
     return acc;
 }
 
-/* exact distance key used by the search (Alg. 2, "compute the distance") */
+/* exact distance key used by the search (Alg. 2, exact-distance step) */
 float orc_key(uint32_t d, const float *x, const float *y) {
     return (float)orc_sqdist64(d, x, y);
 }
 
-/* q' = Q q  (Alg. 2, "Set q <- Qq") */
+/* q' = Q q  (Alg. 2, rotation step) */
 void orc_rotate(uint32_t d, const float *rot, const float *x, float *out) {
     for (uint32_t j = 0; j < d; ++j) {
         double acc = 0.0;
@@ -102,7 +102,7 @@ void orc_normalise(uint32_t d, const float *x, float *out) {
     for (uint32_t k = 0; k < d; ++k) out[k] = (float)((double)x[k] / nrm);
 }
 
-/* projection table T[l][j] = <q_l, r_jl>  (Alg. 2, "build a projection table") */
+/* projection table T[l][j] = <q_l, r_jl>  (Alg. 2, projection-table step) */
 void orc_table(uint32_t d, uint32_t P, const float *cb, const float *q, float *T, double *T64) {
     uint32_t ds = d / P;
     for (uint32_t l = 0; l < P; ++l)

@@ -13,12 +13,15 @@ L2, IP, COS = 0, 1, 2
 FLAG_NO_PRT = 1
 FLAG_NO_PES = 2
 FLAG_FP16_VECTORS = 4
+FLAG_KEEP_ORDER = 8
+FLAG_EXACT_TEST_COUNT = 16
 _METRICS = {"l2": L2, "ip": IP, "cos": COS, "cosine": COS, L2: L2, IP: IP, COS: COS}
 
 EXPORTED_SYMBOLS = (
     "pag_build", "pag_search", "pag_insert", "pag_free", "pag_describe", "pag_export", "pag_import",
     "pag_get_counters", "pag_reset_counters", "pag_set_search_options", "pag_set_seen_capacity_log2",
-    "pag_prepare_queries", "pag_exact_distances", "pag_screen", "pag_edge_info", "pag_measure_row_reads",
+    "pag_prepare_queries", "pag_exact_distances", "pag_screen", "pag_edge_info", "pag_insertion_candidates",
+    "pag_measure_row_reads",
     "pag_searcher_create", "pag_searcher_search", "pag_searcher_get_counters", "pag_searcher_free",
     "pag_last_error",
 )
@@ -48,7 +51,7 @@ class _Counters(C.Structure):
                [(k, C.c_uint64) for k in ("queries", "hops", "tests", "passes", "exact", "rounds",
                                           "rf_overflow", "rt_overflow", "seen_spills")] + \
                [("last_search_kernel_ms", C.c_double), ("last_prepare_ms", C.c_double),
-                ("last_build_ms", C.c_double), ("phase_cycles", C.c_uint64 * 6)]
+                ("last_build_ms", C.c_double), ("phase_cycles", C.c_uint64 * 6), ("relinked_batches", C.c_uint64)]
 
 
 _lib = None
@@ -121,7 +124,8 @@ class PagIndex:
 
     @classmethod
     def from_arrays(cls, vectors, adj, a, c, e2, codes, rotation, codebooks, entry, metric="l2",
-                    ef_construction=100, search_b=0, flags=0, capacity=0, seed=1, stream=None, device="cuda:0"):
+                    ef_construction=100, search_b=0, flags=0, capacity=0, seed=1, stream=None, device="cuda:0",
+                    insert_subbatch=0):
         """pag_import from host numpy arrays (shapes as in pag_arrays)."""
         import torch
         lib = load_library()
@@ -139,7 +143,7 @@ class PagIndex:
                       _np_ptr(a), _np_ptr(c), _np_ptr(e2), _np_ptr(codes), _np_ptr(rotation), _np_ptr(codebooks),
                       _np_ptr(entry))
         with torch.cuda.device(device):
-            p = cls._params(metric, deg, P, ef_construction, search_b, 0, flags, capacity, seed, stream)
+            p = cls._params(metric, deg, P, ef_construction, search_b, insert_subbatch, flags, capacity, seed, stream)
             h = C.c_void_p()
             _check(lib.pag_import(C.byref(arr), C.byref(p), C.byref(h)), "pag_import")
         return cls(h, torch.device(device))
@@ -256,6 +260,19 @@ class PagIndex:
         _check(load_library().pag_measure_row_reads(self._h, C.c_uint64(rows), C.c_int(int(scattered)),
                                                     C.byref(out)), "pag_measure_row_reads")
         return out.value
+
+    def insertion_candidates(self, X, ef_construction):
+        """pag_insertion_candidates for the raw vectors X (device): per vector R_L (ids, keys, count) and the PES
+        buffer H(v) (ids, keys, count) as host arrays.  ef_construction must be the index's own efC."""
+        m = X.shape[0]
+        deg = self.describe()["deg"]
+        ci, ck = np.empty((m, ef_construction), np.uint32), np.empty((m, ef_construction), np.float32)
+        hi, hk = np.empty((m, deg), np.uint32), np.empty((m, deg), np.float32)
+        cn, hn = np.empty(m, np.uint32), np.empty(m, np.uint32)
+        _check(load_library().pag_insertion_candidates(self._h, _dev_f32(X, "X"), C.c_uint64(m), _np_ptr(ci), _np_ptr(ck),
+                                                       _np_ptr(cn), _np_ptr(hi), _np_ptr(hk), _np_ptr(hn)),
+               "pag_insertion_candidates")
+        return ci, ck, cn, hi, hk, hn
 
     def edge_info(self, node_begin, node_end):
         m = self.describe()

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstring>
 #include <functional>
+#include <new>
 #include <thread>
 #include <vector>
 
@@ -144,7 +145,23 @@ int check_params(const pag_params* p) {
     PAG_CHECK(p->metric >= PAG_L2 && p->metric <= PAG_COS, PAG_EINVAL, "unknown metric");
     PAG_CHECK(p->ef_construction >= 1, PAG_EINVAL, "ef_construction must be >= 1");
     PAG_CHECK(p->search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 1024 is not built");
+    // the reverse-edge pairs of one batch (2 * max_degree per vector) are counted in 32 bits
+    PAG_CHECK(p->insert_subbatch <= (1u << 20), PAG_EUNSUPPORTED, "insert_subbatch above 2^20 is not built");
     return PAG_OK;
+}
+
+// Runs the body of an entry point; no exception leaves the library (host allocations can throw).
+template <typename F>
+int guarded(const char* what, F&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        pag_set_error(std::string(what) + ": host allocation failed");
+        return PAG_ENOMEM;
+    } catch (const std::exception& e) {
+        pag_set_error(std::string(what) + ": " + e.what());
+        return PAG_EINVAL;
+    }
 }
 
 template <typename T>
@@ -262,25 +279,31 @@ extern "C" int pag_build(const float* D, uint64_t n, uint32_t d, const pag_param
     if ((rc = make_layout(d, params->num_subspaces, params->max_degree, &L))) return rc;
     PAG_CHECK(!(params->flags & PAG_FLAG_FP16_VECTORS) || d % 8 == 0, PAG_EUNSUPPORTED,
               "PAG_FLAG_FP16_VECTORS needs d % 8 == 0");
-    pag_index* ix = new_index(params, d);
-    ix->L = L;
-    ix->capacity = std::max<u64>(params->capacity, n);
-    if (ix->capacity >= (1ull << 31)) { pag_free(ix); pag_set_error("capacity must be below 2^31"); return PAG_EUNSUPPORTED; }
-    const auto t0 = std::chrono::steady_clock::now();
-    if ((rc = alloc_index(ix))) { pag_free(ix); return rc; }
-    std::vector<float> rot, cb;
-    make_transform(d, params->seed, rot);
-    make_codebooks(d, L.P, params->seed, cb);
-    hipError_t e = hipMemcpyAsync(ix->rot, rot.data(), rot.size() * 4, hipMemcpyHostToDevice, ix->stream);
-    if (e == hipSuccess) e = hipMemcpyAsync(ix->cb, cb.data(), cb.size() * 4, hipMemcpyHostToDevice, ix->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(ix->rec, 0xFF, ix->capacity * L.rec_bytes, ix->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(ix->stream);
-    if (e != hipSuccess) { pag_free(ix); pag_set_error(std::string("pag_build upload: ") + hipGetErrorString(e)); return PAG_EHIP; }
-    if ((rc = ingest(ix, D, n, 0))) { pag_free(ix); return rc; }
-    ix->n = 0;
-    if ((rc = pag_build_range(ix, 0, n))) { pag_free(ix); return rc; }
-    ix->n = n;
-    ix->last_build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    pag_index* ix = nullptr;
+    rc = guarded("pag_build", [&]() -> int {
+        int rc;
+        ix = new_index(params, d);
+        ix->L = L;
+        ix->capacity = std::max<u64>(params->capacity, n);
+        if (ix->capacity >= (1ull << 31)) { pag_set_error("capacity must be below 2^31"); return PAG_EUNSUPPORTED; }
+        const auto t0 = std::chrono::steady_clock::now();
+        if ((rc = alloc_index(ix))) return rc;
+        std::vector<float> rot, cb;
+        make_transform(d, params->seed, rot);
+        make_codebooks(d, L.P, params->seed, cb);
+        hipError_t e = hipMemcpyAsync(ix->rot, rot.data(), rot.size() * 4, hipMemcpyHostToDevice, ix->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(ix->cb, cb.data(), cb.size() * 4, hipMemcpyHostToDevice, ix->stream);
+        if (e == hipSuccess) e = hipMemsetAsync(ix->rec, 0xFF, ix->capacity * L.rec_bytes, ix->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ix->stream);
+        if (e != hipSuccess) { pag_set_error(std::string("pag_build upload: ") + hipGetErrorString(e)); return PAG_EHIP; }
+        if ((rc = ingest(ix, D, n, 0))) return rc;
+        ix->n = 0;
+        if ((rc = pag_build_range(ix, 0, n))) return rc;
+        ix->n = n;
+        ix->last_build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        return PAG_OK;
+    });
+    if (rc) { pag_free(ix); return rc; }
     *out = ix;
     return PAG_OK;
 }
@@ -290,11 +313,21 @@ extern "C" int pag_insert(pag_index* ix, const float* X, uint64_t m) {
     if (m == 0) return PAG_OK;
     PAG_CHECK(X != nullptr, PAG_EINVAL, "X is null");
     PAG_CHECK(ix->n + m <= ix->capacity, PAG_ECAPACITY, "pag_insert: capacity exceeded");
+    PAG_CHECK(!ix->insert_failed, PAG_EINVAL, "pag_insert: an earlier pag_insert on this index failed half way; it takes no more vectors");
     DeviceGuard g(ix->device);
     const auto t0 = std::chrono::steady_clock::now();
-    int rc;
-    if ((rc = ingest(ix, X, m, ix->n))) return rc;
-    if ((rc = pag_build_range(ix, ix->n, ix->n + m))) return rc;
+    const u32 entry_before = ix->n_entry;
+    int rc = guarded("pag_insert", [&]() -> int {
+        int rc;
+        if ((rc = ingest(ix, X, m, ix->n))) return rc;
+        return pag_build_range(ix, ix->n, ix->n + m);
+    });
+    if (rc) {
+        // searches go on over the n published nodes (ids >= n are ignored); the entry list is theirs again
+        ix->n_entry = entry_before;
+        ix->insert_failed = 1;
+        return rc;
+    }
     // publish: every kernel of the insertion has finished (pag_build_range synchronises), searchers may now see the nodes
     __atomic_store_n(&ix->n, ix->n + m, __ATOMIC_RELEASE);
     ix->last_build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
@@ -309,7 +342,7 @@ extern "C" int pag_describe(const pag_index* ix, pag_arrays* out) {
     return PAG_OK;
 }
 
-extern "C" int pag_export(const pag_index* ix, pag_arrays* out) {
+static int export_impl(const pag_index* ix, pag_arrays* out) {
     PAG_CHECK(ix && out, PAG_EINVAL, "null argument");
     PAG_CHECK(out->struct_size == sizeof(pag_arrays), PAG_EINVAL, "pag_arrays.struct_size does not match this library");
     PAG_CHECK(out->vectors && out->adj && out->a && out->c && out->e2 && out->codes && out->rotation &&
@@ -364,7 +397,11 @@ extern "C" int pag_export(const pag_index* ix, pag_arrays* out) {
     return PAG_OK;
 }
 
-extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_index** out) {
+extern "C" int pag_export(const pag_index* ix, pag_arrays* out) {
+    return guarded("pag_export", [&]() { return export_impl(ix, out); });
+}
+
+static int import_impl(const pag_arrays* in, const pag_params* params, pag_index** out) {
     PAG_CHECK(out != nullptr, PAG_EINVAL, "out is null");
     *out = nullptr;
     int rc = check_params(params);
@@ -395,6 +432,9 @@ extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_in
     for (u64 i = 0; i < n * L.deg * L.P; ++i) PAG_CHECK(in->codes[i] < PAG_NCODE, PAG_EINVAL, "pag_import: code above 15");
     PAG_CHECK(!(params->flags & PAG_FLAG_FP16_VECTORS) || in->d % 8 == 0, PAG_EUNSUPPORTED,
               "PAG_FLAG_FP16_VECTORS needs d % 8 == 0");
+    // host staging first: nothing below this point allocates host memory
+    const u64 slab = 1 << 16;
+    std::vector<uint8_t> buf(std::min<u64>(slab, n) * L.rec_bytes);
     pag_index* ix = new_index(params, in->d);
     ix->metric = in->metric;
     ix->L = L;
@@ -421,8 +461,6 @@ extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_in
     if ((e = hipMemcpy(ix->cb, in->codebooks, (u64)L.P * PAG_NCODE * L.dsub * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
     if ((e = hipMemcpy(ix->entry, in->entry, in->n_entry * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(e);
     ix->n_entry = in->n_entry;
-    const u64 slab = 1 << 16;
-    std::vector<uint8_t> buf(std::min<u64>(slab, n) * L.rec_bytes);
     for (u64 s = 0; s < n; s += slab) {
         const u64 cnt = std::min<u64>(slab, n - s);
         std::memset(buf.data(), 0, cnt * L.rec_bytes);
@@ -444,6 +482,11 @@ extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_in
     return PAG_OK;
 }
 
+extern "C" int pag_import(const pag_arrays* in, const pag_params* params, pag_index** out) {
+    if (out) *out = nullptr;
+    return guarded("pag_import", [&]() { return import_impl(in, params, out); });
+}
+
 extern "C" int pag_get_counters(const pag_index* ix, pag_counters* out) {
     PAG_CHECK(ix && out, PAG_EINVAL, "null argument");
     PAG_CHECK(out->struct_size == sizeof(pag_counters), PAG_EINVAL, "pag_counters.struct_size does not match this library");
@@ -459,6 +502,7 @@ extern "C" int pag_get_counters(const pag_index* ix, pag_counters* out) {
     out->last_prepare_ms = ix->last_prepare_ms;
     out->last_build_ms = ix->last_build_ms;
     for (int i = 0; i < 6; ++i) out->phase_cycles[i] = h[CTR_PHASE0 + i];
+    out->relinked_batches = ix->relinked_batches;
     return PAG_OK;
 }
 
@@ -475,7 +519,8 @@ extern "C" int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t
     PAG_CHECK(ix, PAG_EINVAL, "null argument");
     PAG_CHECK(search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 1024 is not built");
     ix->search_b = search_b;
-    ix->flags = (ix->flags & PAG_FLAG_NO_PES) | (flags & PAG_FLAG_NO_PRT);   // index-time bits stay as built
+    const u32 search_bits = PAG_FLAG_NO_PRT | PAG_FLAG_EXACT_TEST_COUNT;
+    ix->flags = (ix->flags & ~search_bits) | (flags & search_bits);           // index-time bits stay as built
     return PAG_OK;
 }
 
@@ -490,16 +535,22 @@ extern "C" int pag_set_seen_capacity_log2(pag_index* ix, uint32_t log2_slots) {
 // search
 // ---------------------------------------------------------------------------------------------
 
-static int prepare(pag_index* ix, const float* Q, u64 nq, float* qrot, float* tables) {
+// normalisation (COS, into `norm`), rotation and projection tables of nq queries; allocates nothing
+static int prepare_into(const pag_index* ix, const float* Q, u64 nq, float* norm, float* qrot, float* tables) {
     const float* src = Q;
     int rc;
     if (ix->metric == PAG_COS) {
-        if ((rc = ensure_ws(&ix->ws_norm, &ix->ws_norm_cap, nq * ix->L.d))) return rc;
-        if ((rc = pag_launch_normalise(ix->stream, Q, nq, ix->L.d, ix->ws_norm))) return rc;
-        src = ix->ws_norm;
+        if ((rc = pag_launch_normalise(ix->stream, Q, nq, ix->L.d, norm))) return rc;
+        src = norm;
     }
     if ((rc = pag_launch_rotate(ix->stream, src, nq, ix->L.d, ix->rot, qrot))) return rc;
     return pag_launch_tables(ix->stream, qrot, nq, ix->L, ix->cb, tables);
+}
+
+static int prepare(pag_index* ix, const float* Q, u64 nq, float* qrot, float* tables) {
+    int rc;
+    if (ix->metric == PAG_COS && (rc = ensure_ws(&ix->ws_norm, &ix->ws_norm_cap, nq * ix->L.d))) return rc;
+    return prepare_into(ix, Q, nq, ix->ws_norm, qrot, tables);
 }
 
 // Seen-set sizing.  A search expected to compute at most ~1000 exact distances (entries + a few per
@@ -518,8 +569,9 @@ static void seen_sizes_for(const pag_index* ix, u32 ef, u32 b, u32* hlog, u32* b
     if (ix->seen_log2) *hlog = ix->seen_log2;
 }
 
-// Fills the part of SearchArgs that depends only on the index and (b, ef); shared with indexing.
-int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid) {
+// Plans a search: fills the part of SearchArgs that depends only on the index and (b, ef), the LDS carve-up and the
+// largest useful grid.  Allocates nothing.
+static int search_plan(const pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid) {
     const pag_layout& L = ix->L;
     std::memset((void*)a, 0, sizeof(*a));
     a->vec = ix->vec; a->rec = ix->rec; a->entry = ix->entry;
@@ -558,6 +610,13 @@ int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, 
     }
     // per-wave spill bitmaps of the seen set: one bit per node, rounded to 16 bytes
     a->bitmap_words = ((u64)ix->capacity + 127) / 128 * 4;
+    return PAG_OK;
+}
+
+// The plan plus the workspaces it needs (grown on demand); shared with indexing.
+int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, u32* lds, int* grid) {
+    int rc = search_plan(ix, b, ef, n_limit, a, lds, grid);
+    if (rc) return rc;
     const u64 need = (u64)*grid * a->bitmap_words;
     if (ix->ws_bitmap_cap < need) {
         // a fresh buffer starts dirty: clear it once; every wave leaves its slice clean afterwards
@@ -729,8 +788,8 @@ extern "C" int pag_screen(const pag_index* cix, const float* tables, uint64_t nq
     return PAG_OK;
 }
 
-extern "C" int pag_edge_info(const pag_index* cix, uint64_t node_begin, uint64_t node_end, uint8_t* codes,
-                             float* a, float* c, float* e2) {
+static int edge_info_impl(const pag_index* cix, uint64_t node_begin, uint64_t node_end, uint8_t* codes,
+                          float* a, float* c, float* e2) {
     pag_index* ix = const_cast<pag_index*>(cix);
     PAG_CHECK(ix && codes && a && c && e2, PAG_EINVAL, "null argument");
     PAG_CHECK(node_begin <= node_end && node_end <= ix->n, PAG_EINVAL, "node range out of bounds");
@@ -742,10 +801,10 @@ extern "C" int pag_edge_info(const pag_index* cix, uint64_t node_begin, uint64_t
     uint8_t* srec = nullptr;
     float* se2 = nullptr;
     int rc;
+    std::vector<uint8_t> buf(m * L.rec_bytes);      // host staging before anything is held on the device
+    std::vector<float> he2(m * L.deg);
     if ((rc = dev_alloc(&srec, m * L.rec_bytes))) return rc;
     if ((rc = dev_alloc(&se2, m * L.deg))) { (void)hipFree(srec); return rc; }
-    std::vector<uint8_t> buf(m * L.rec_bytes);
-    std::vector<float> he2(m * L.deg);
     hipError_t e = hipMemcpyAsync(srec, ix->rec + node_begin * L.rec_bytes, m * L.rec_bytes, hipMemcpyDeviceToDevice, ix->stream);
     if (e == hipSuccess) rc = pag_launch_edge_info_nodes(ix->stream, ix, node_begin, node_end, srec, se2, node_begin);
     if (e == hipSuccess && rc == PAG_OK) e = hipStreamSynchronize(ix->stream);
@@ -765,6 +824,11 @@ extern "C" int pag_edge_info(const pag_index* cix, uint64_t node_begin, uint64_t
                 codes[(i * L.deg + ed) * L.P + l] = (uint8_t)((cw[ed * L.cw + l / 8] >> (4 * (l % 8))) & 15u);
     }
     return PAG_OK;
+}
+
+extern "C" int pag_edge_info(const pag_index* cix, uint64_t node_begin, uint64_t node_end, uint8_t* codes,
+                             float* a, float* c, float* e2) {
+    return guarded("pag_edge_info", [&]() { return edge_info_impl(cix, node_begin, node_end, codes, a, c, e2); });
 }
 
 extern "C" int pag_measure_row_reads(const pag_index* cix, uint64_t rows, int scattered, double* gb_per_s) {

@@ -11,6 +11,8 @@
 #include <hipcub/hipcub.hpp>
 
 #include <algorithm>
+#include <cstring>
+#include <new>
 #include <vector>
 
 #include "pag_internal.h"
@@ -420,6 +422,57 @@ struct BuildWs {
 
 }  // namespace
 
+// Workspaces of the insertion search for batches of up to max_batch nodes.
+static int alloc_candidate_ws(BuildWs& ws, u64 max_batch, u32 cand_cap, u32 deg, bool use_pes, hipStream_t s) {
+    if (max_batch * cand_cap > 0x7FFFFFFFull) { pag_set_error("build: batch x ef_construction exceeds 2^31 candidate slots"); return PAG_EUNSUPPORTED; }
+    PAG_ALLOC(ws.cand, max_batch * cand_cap * 8);
+    PAG_ALLOC(ws.cand_sorted, max_batch * cand_cap * 8);
+    PAG_ALLOC(ws.cand_cnt, max_batch * 4);
+    if (use_pes) PAG_ALLOC(ws.pes, max_batch * deg * 8);
+    PAG_ALLOC(ws.seg_begin, max_batch * 4);
+    PAG_ALLOC(ws.seg_end, max_batch * 4);
+    PAG_HIP(hipcub::DeviceSegmentedRadixSort::SortKeys(nullptr, ws.seg_bytes, ws.cand, ws.cand_sorted, (int)(max_batch * cand_cap),
+                                                       (int)max_batch, ws.seg_begin, ws.seg_end, 1, 64, s));
+    PAG_ALLOC(ws.seg_tmp, ws.seg_bytes);
+    return PAG_OK;
+}
+
+// The search of Alg. 1 for m points (rotated rows `qrot`) over the nodes below n_limit: tables, the PRT-TFB search in
+// indexing mode (ef = efC, b = min(efC, 100), every round's W collected, PES screening into ws.pes), then every
+// point's candidates sorted by (dist, id) -- bits 1..63 of the keys, the visited flag aside -- into ws.cand_sorted.
+static int search_candidates(pag_index* ix, BuildWs& ws, const float* qrot, u64 m, u32 b, u32 cand_cap, u64 n_limit) {
+    const pag_layout& L = ix->L;
+    hipStream_t s = ix->stream;
+    int rc;
+    if ((rc = pag_launch_tables(s, qrot, m, L, ix->cb, ix->ws_tab))) return rc;
+    SearchArgs a;
+    u32 lds = 0;
+    int grid = 0;
+    if ((rc = pag_search_common(ix, b, ix->efC, n_limit, &a, &lds, &grid))) return rc;
+    a.qrot = qrot; a.tables = ix->ws_tab; a.nq = (u32)m; a.K = b;
+    a.flags &= ~(u32)PAG_FLAG_NO_PRT;          // indexing always runs with the projection test on
+    a.cand = ws.cand; a.cand_cnt = ws.cand_cnt; a.cand_cap = cand_cap;
+    a.pes = ws.pes;
+    if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
+    if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
+    hipLaunchKernelGGL(k_cand_segments, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, ws.cand_cnt, (u32)m, cand_cap,
+                       ws.seg_begin, ws.seg_end);
+    PAG_HIP(hipGetLastError());
+    PAG_HIP(hipcub::DeviceSegmentedRadixSort::SortKeys(ws.seg_tmp, ws.seg_bytes, ws.cand, ws.cand_sorted, (int)(m * cand_cap), (int)m,
+                                                       ws.seg_begin, ws.seg_end, 1, 64, s));
+    return PAG_OK;
+}
+
+// grows a workspace of the index to `need` floats
+static int ensure_floats(float** p, u64* cap, u64 need) {
+    if (*cap >= need) return PAG_OK;
+    if (*p) (void)hipFree(*p);
+    *p = nullptr; *cap = 0;
+    PAG_ALLOC(*p, need * 4);
+    *cap = need;
+    return PAG_OK;
+}
+
 // splitmix64: the generator behind the insertion order
 static inline u64 next_random(u64& state) {
     u64 z = (state += 0x9E3779B97F4A7C15ull);
@@ -447,10 +500,11 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         std::vector<u32> order(count);
         for (u64 i = 0; i < count; ++i) order[i] = (u32)(n_begin + i);
         u64 state = ix->seed ^ (0xA0761D6478BD642Full * (n_begin + 1));
-        for (u64 i = count - 1; i > 0; --i) {                 // Fisher-Yates
-            const u64 j = next_random(state) % (i + 1);
-            std::swap(order[i], order[j]);
-        }
+        if (!(ix->flags & PAG_FLAG_KEEP_ORDER))
+            for (u64 i = count - 1; i > 0; --i) {             // Fisher-Yates
+                const u64 j = next_random(state) % (i + 1);
+                std::swap(order[i], order[j]);
+            }
         PAG_ALLOC(ws.order, count * 4);
         PAG_HIP(hipMemcpyAsync(ws.order, order.data(), count * 4, hipMemcpyHostToDevice, s));
         // the entry list grows with the first nodes of the order until it holds 1024
@@ -479,11 +533,8 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
 
     u64 max_batch = ix->subbatch ? ix->subbatch : std::min<u64>(16384, std::max<u64>(1024, n_end / 50));
     max_batch = std::min<u64>(max_batch, count);       // a small insertion gets small workspaces
-    PAG_ALLOC(ws.cand, max_batch * cand_cap * 8);
-    PAG_ALLOC(ws.cand_sorted, max_batch * cand_cap * 8);
-    PAG_ALLOC(ws.cand_cnt, max_batch * 4);
     const bool use_pes = !(ix->flags & PAG_FLAG_NO_PES);
-    if (use_pes) PAG_ALLOC(ws.pes, max_batch * L.deg * 8);
+    if ((rc = alloc_candidate_ws(ws, max_batch, cand_cap, L.deg, use_pes, s))) return rc;
     const u64 max_pairs = max_batch * L.deg * (use_pes ? 2 : 1);
     PAG_ALLOC(ws.rk_in, max_pairs * 8);
     PAG_ALLOC(ws.rk_out, max_pairs * 8);
@@ -494,56 +545,21 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     PAG_HIP(hipcub::DeviceRadixSort::SortPairs(nullptr, ws.sort_bytes, ws.rk_in, ws.rk_out, ws.rv_in, ws.rv_out,
                                                (int)max_pairs, 0, 64, s));
     PAG_ALLOC(ws.sort_tmp, ws.sort_bytes);
-    PAG_ALLOC(ws.seg_begin, max_batch * 4);
-    PAG_ALLOC(ws.seg_end, max_batch * 4);
-    if (max_batch * cand_cap > 0x7FFFFFFFull) { pag_set_error("build: batch x ef_construction exceeds 2^31 candidate slots"); return PAG_EUNSUPPORTED; }
-    PAG_HIP(hipcub::DeviceSegmentedRadixSort::SortKeys(nullptr, ws.seg_bytes, ws.cand, ws.cand_sorted, (int)(max_batch * cand_cap),
-                                                       (int)max_batch, ws.seg_begin, ws.seg_end, 1, 64, s));
-    PAG_ALLOC(ws.seg_tmp, ws.seg_bytes);
-    if (ix->ws_qrot_cap < max_batch * L.d) {            // the rows of a batch, gathered: its queries
-        if (ix->ws_qrot) (void)hipFree(ix->ws_qrot);
-        ix->ws_qrot = nullptr; ix->ws_qrot_cap = 0;
-        PAG_ALLOC(ix->ws_qrot, max_batch * L.d * 4);
-        ix->ws_qrot_cap = max_batch * L.d;
-    }
-    {   // table workspace for the largest batch
-        const u64 need = max_batch * L.Ppad * PAG_NCODE;
-        if (ix->ws_tab_cap < need) {
-            if (ix->ws_tab) (void)hipFree(ix->ws_tab);
-            ix->ws_tab = nullptr; ix->ws_tab_cap = 0;
-            PAG_ALLOC(ix->ws_tab, need * 4);
-            ix->ws_tab_cap = need;
-        }
-    }
+    // the rows of a batch, gathered (its queries), and their tables
+    if ((rc = ensure_floats(&ix->ws_qrot, &ix->ws_qrot_cap, max_batch * L.d))) return rc;
+    if ((rc = ensure_floats(&ix->ws_tab, &ix->ws_tab_cap, max_batch * L.Ppad * PAG_NCODE))) return rc;
     constexpr u32 kDensitySamples = 128, kDensityProbes = 2048;
     constexpr double kCrowdedRatio = 4.0;
     PAG_ALLOC(ws.density, kDensitySamples * 2 * 4);
     // one linking pass over `m` listed nodes: search, RobustPrune, reverse edges, inference information
     auto link = [&](const u32* nodes, u64 m) -> int {
         int rc;
-        // 1. the new nodes are their own queries (already rotated): rows gathered and widened to fp32, then their tables
+        // 1. the new nodes are their own queries (already rotated): rows gathered and widened to fp32
         hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)m), dim3(64), 0, s, pag_vecs_of(ix), L.d, nodes, ix->ws_qrot);
         PAG_HIP(hipGetLastError());
-        const float* qrot = ix->ws_qrot;
-        if ((rc = pag_launch_tables(s, qrot, m, L, ix->cb, ix->ws_tab))) return rc;
-        // 2. PRT-TFB search of the graph built so far.  Nodes that are not inserted yet have empty records and no
-        //    in-edges, and the entry list holds inserted nodes only, so they cannot be reached.
-        SearchArgs a;
-        u32 lds = 0;
-        int grid = 0;
-        if ((rc = pag_search_common(ix, b, ix->efC, n_end, &a, &lds, &grid))) return rc;
-        a.qrot = qrot; a.tables = ix->ws_tab; a.nq = (u32)m; a.K = b;
-        a.flags &= ~(u32)PAG_FLAG_NO_PRT;          // indexing always runs with the projection test on
-        a.cand = ws.cand; a.cand_cnt = ws.cand_cnt; a.cand_cap = cand_cap;
-        a.pes = ws.pes;
-        if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
-        if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
-        // 3. candidates of every new node sorted by (dist, id): bits 1..63 of the keys, the visited flag aside
-        hipLaunchKernelGGL(k_cand_segments, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, ws.cand_cnt, (u32)m, cand_cap,
-                           ws.seg_begin, ws.seg_end);
-        PAG_HIP(hipGetLastError());
-        PAG_HIP(hipcub::DeviceSegmentedRadixSort::SortKeys(ws.seg_tmp, ws.seg_bytes, ws.cand, ws.cand_sorted, (int)(m * cand_cap), (int)m,
-                                                           ws.seg_begin, ws.seg_end, 1, 64, s));
+        // 2. + 3. PRT-TFB search of the graph built so far, candidates sorted.  Nodes that are not inserted yet have
+        //    empty records and no in-edges, and the entry list holds inserted nodes only, so they cannot be reached.
+        if ((rc = search_candidates(ix, ws, ix->ws_qrot, m, b, cand_cap, n_end))) return rc;
         //    RobustPrune -> N_out(v), reverse pairs
         {
             const u32 plds = 2 * L.d * 4 + L.deg * 4;
@@ -593,9 +609,91 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
             const bool crowded = mates >= 32.0 && mates > kCrowdedRatio * std::max(older, 1.0);
             if (crowded) {
                 if ((rc = link(nodes, m))) return rc;
+                ix->relinked_batches++;
             }
         }
     }
     PAG_HIP(hipStreamSynchronize(s));
     return PAG_OK;
+}
+
+// What inserting each of the m raw vectors X into the index as it stands would start from (Alg. 1, the search of one
+// insertion; Eq. 5): R_L cut to efC and the PES buffer H(v), copied to host arrays.  The index is not changed.
+extern "C" int pag_insertion_candidates(const pag_index* cix, const float* X, uint64_t m, uint32_t* cand_ids,
+                                        float* cand_keys, uint32_t* cand_count, uint32_t* pes_ids, float* pes_keys,
+                                        uint32_t* pes_count) {
+    pag_index* ix = const_cast<pag_index*>(cix);   // workspaces are mutable state of the handle
+    if (!ix || !X || !cand_ids || !cand_keys || !cand_count || !pes_ids || !pes_keys || !pes_count) {
+        pag_set_error("pag_insertion_candidates: null argument");
+        return PAG_EINVAL;
+    }
+    if (m == 0) return PAG_OK;
+    int prev = -1;
+    (void)hipGetDevice(&prev);
+    if (prev != ix->device) (void)hipSetDevice(ix->device);
+    struct Restore { int prev, cur; ~Restore() { if (prev >= 0 && prev != cur) (void)hipSetDevice(prev); } } restore{prev, ix->device};
+    try {
+        const pag_layout& L = ix->L;
+        hipStream_t s = ix->stream;
+        const u32 efC = ix->efC;
+        const u32 b = std::min<u32>(efC, 100);
+        const u32 Rmax = std::max<u32>(1, (efC + b - 1) / b);
+        const u32 cand_cap = Rmax * b;
+        const bool use_pes = !(ix->flags & PAG_FLAG_NO_PES);
+        const u64 chunk = std::min<u64>(m, 4096);
+        int rc;
+        BuildWs ws;
+        if ((rc = alloc_candidate_ws(ws, chunk, cand_cap, L.deg, use_pes, s))) return rc;
+        if ((rc = ensure_floats(&ix->ws_qrot, &ix->ws_qrot_cap, chunk * L.d))) return rc;
+        if ((rc = ensure_floats(&ix->ws_tab, &ix->ws_tab_cap, chunk * L.Ppad * PAG_NCODE))) return rc;
+        if (ix->metric == PAG_COS && (rc = ensure_floats(&ix->ws_norm, &ix->ws_norm_cap, chunk * L.d))) return rc;
+        __half* half_rows = nullptr;
+        struct FreeHalf { __half*& p; ~FreeHalf() { if (p) (void)hipFree(p); } } free_half{half_rows};
+        if (ix->vec_half) PAG_ALLOC(half_rows, chunk * L.d * 2);
+        std::vector<u64> keys(chunk * cand_cap), hk(use_pes ? chunk * L.deg : 0);
+        std::vector<u32> cnt(chunk);
+        for (u64 c0 = 0; c0 < m; c0 += chunk) {
+            const u64 cm = std::min<u64>(chunk, m - c0);
+            // the row the vector would be stored as: normalised (COS), rotated, rounded if the store is 16-bit
+            const float* src = X + c0 * L.d;
+            if (ix->metric == PAG_COS) {
+                if ((rc = pag_launch_normalise(s, src, cm, L.d, ix->ws_norm))) return rc;
+                src = ix->ws_norm;
+            }
+            if ((rc = pag_launch_rotate(s, src, cm, L.d, ix->rot, ix->ws_qrot))) return rc;
+            if (ix->vec_half) {
+                if ((rc = pag_launch_convert(s, ix->ws_qrot, 0, half_rows, 1, cm * L.d))) return rc;
+                if ((rc = pag_launch_convert(s, half_rows, 1, ix->ws_qrot, 0, cm * L.d))) return rc;
+            }
+            if ((rc = search_candidates(ix, ws, ix->ws_qrot, cm, b, cand_cap, ix->n))) return rc;
+            PAG_HIP(hipMemcpyAsync(keys.data(), ws.cand_sorted, cm * cand_cap * 8, hipMemcpyDeviceToHost, s));
+            PAG_HIP(hipMemcpyAsync(cnt.data(), ws.cand_cnt, cm * 4, hipMemcpyDeviceToHost, s));
+            if (use_pes) PAG_HIP(hipMemcpyAsync(hk.data(), ws.pes, cm * L.deg * 8, hipMemcpyDeviceToHost, s));
+            PAG_HIP(hipStreamSynchronize(s));
+            for (u64 i = 0; i < cm; ++i) {
+                const u32 nc = std::min<u32>(std::min<u32>(cnt[i], cand_cap), efC);
+                cand_count[c0 + i] = nc;
+                for (u32 k = 0; k < efC; ++k) {
+                    const u64 key = k < nc ? keys[i * cand_cap + k] : 0ull;
+                    cand_ids[(c0 + i) * efC + k] = k < nc ? (u32)(key & 0xFFFFFFFFull) >> 1 : PAG_EMPTY;
+                    const u32 bits = (u32)(key >> 32);
+                    std::memcpy(&cand_keys[(c0 + i) * efC + k], &bits, 4);
+                }
+                u32 nh = 0;
+                for (u32 k = 0; k < L.deg; ++k) {
+                    const u64 key = use_pes ? hk[i * L.deg + k] : PAG_KEY_INVALID;
+                    const bool ok = key != PAG_KEY_INVALID;
+                    pes_ids[(c0 + i) * L.deg + k] = ok ? (u32)(key & 0xFFFFFFFFull) >> 1 : PAG_EMPTY;
+                    const u32 bits = ok ? (u32)(key >> 32) : 0u;
+                    std::memcpy(&pes_keys[(c0 + i) * L.deg + k], &bits, 4);
+                    nh += ok ? 1u : 0u;
+                }
+                pes_count[c0 + i] = nh;
+            }
+        }
+        return PAG_OK;
+    } catch (const std::bad_alloc&) {
+        pag_set_error("pag_insertion_candidates: host allocation failed");
+        return PAG_ENOMEM;
+    }
 }

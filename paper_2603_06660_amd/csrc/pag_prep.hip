@@ -1,6 +1,6 @@
 // Query / data preparation kernels: normalisation (cosine), rotation by the fixed orthogonal
-// transform Q (Alg. 1 "replace every x by Qx", Alg. 2 "q <- Qq") and the projection tables
-// (Alg. 2 "compute all <q_l, r_jl>").  All sums are fp64 sums of exact fp32 x fp32 products,
+// transform Q (Alg. 1 and Alg. 2, rotation step) and the projection tables
+// (Alg. 2, projection-table step).  All sums are fp64 sums of exact fp32 x fp32 products,
 // rounded once to fp32, so that they agree with a plain fp64 evaluation to the last bit in all
 // but a vanishing fraction of the outputs.
 #include "pag_internal.h"

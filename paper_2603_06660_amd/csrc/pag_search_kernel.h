@@ -299,7 +299,7 @@ struct Wave {
         if (best_id != PAG_EMPTY) load_record(best_id, pf_id, pf_a, pf_c, pf_cw);
     }
 
-    // exact keys ||q - x_id||^2 (Alg. 2, "compute the distance") for the lanes in `mask`;
+    // exact keys ||q - x_id||^2 (Alg. 2, exact-distance step) for the lanes in `mask`;
     // lane p receives the key of its own id.  Differences in fp32, squares summed in fp64,
     // one rounding to fp32 at the end.  Two buffers of GB vectors each alternate: while one is
     // reduced the other one's loads are in flight.  No load sits inside a branch (a buffer without
@@ -541,7 +541,7 @@ struct Wave {
         s_queries++;
         u32 n_cand = 0;   // indexing mode: entries of R_L written so far
 
-        // ---- b entry nodes (Alg. 2, "insert b entry nodes into W") ----
+        // ---- b entry nodes (Alg. 2, entry step) ----
         {
             u32 ne = A.n_entry < b ? A.n_entry : b;
             for (u32 base = 0; base < ne; base += 64) {
@@ -611,6 +611,15 @@ struct Wave {
                 u32 bm_word = 0;
                 if (A.blog == 0 && n_spill && cand)
                     bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // counting mode of long searches: the second level is consulted for every neighbour, before the
+                // test, so that `tests` counts the unseen neighbours only (same results, more bitmap reads)
+                const bool resolve_first = A.blog != 0 && (A.flags & PAG_FLAG_EXACT_TEST_COUNT);
+                if (resolve_first) {
+                    u32 wd = 0;
+                    if (cand && bloom_maybe(BL, A.blog, id))
+                        wd = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    cand = cand && !((wd >> (id & 31)) & 1u);
+                }
                 // projection test: S = sum_l T[l][code_l] (increasing l), est = D_u + c - 2 a S
                 float est = 0.f;
                 const bool want_pes = A.pes != nullptr;   // indexing: every neighbour's estimate feeds Eq. 5
@@ -621,7 +630,7 @@ struct Wave {
                     }
                     est = __builtin_fmaf(-2.0f * ea, S, Du + ec);
                 }
-                if (A.blog != 0) {
+                if (A.blog != 0 && !resolve_first) {
                     // long searches: only neighbours that pass the test are looked up in the Bloom filter and the bitmap
                     const bool maybe = cand && ((A.flags & PAG_FLAG_NO_PRT) || est < Dmax) && bloom_maybe(BL, A.blog, id);
                     if (maybe) bm_word = __hip_atomic_load(&bitmap[id >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

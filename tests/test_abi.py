@@ -39,14 +39,15 @@ def test_every_declared_entry_point_is_exported(lib):
 def test_struct_layouts_match_the_header(tmp_path):
     from paper_2603_06660_amd import binding
     src = tmp_path / "sizes.c"
-    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "pag.h"\nint main(void){printf("%zu %zu %zu %zu %zu %zu\\n",'
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "pag.h"\nint main(void){printf("%zu %zu %zu %zu %zu %zu %zu\\n",'
                    'sizeof(pag_params),sizeof(pag_arrays),sizeof(pag_counters),offsetof(pag_params,stream),'
-                   'offsetof(pag_arrays,entry),offsetof(pag_counters,last_build_ms));return 0;}\n')
+                   'offsetof(pag_arrays,entry),offsetof(pag_counters,last_build_ms),offsetof(pag_counters,relinked_batches));return 0;}\n')
     exe = tmp_path / "sizes"
     subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     want = [C.sizeof(binding._Params), C.sizeof(binding._Arrays), C.sizeof(binding._Counters),
-            binding._Params.stream.offset, binding._Arrays.entry.offset, binding._Counters.last_build_ms.offset]
+            binding._Params.stream.offset, binding._Arrays.entry.offset, binding._Counters.last_build_ms.offset,
+            binding._Counters.relinked_batches.offset]
     assert got == want
 
 
@@ -65,6 +66,7 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.pag_searcher_create(None, None, C.byref(s)) == -1 and not s.value
     assert lib.pag_searcher_search(None, None, C.c_uint64(1), C.c_uint32(1), C.c_uint32(1), None, None) == -1
     assert lib.pag_searcher_free(None) == 0
+    assert lib.pag_insertion_candidates(None, None, C.c_uint64(1), None, None, None, None, None, None) == -1
 
 
 def test_missing_library_is_an_error(monkeypatch):

@@ -46,15 +46,32 @@ def _assert_search_parity(gix, oix, q, K, efS, gt=None, b=0):
     return gi, gd, oc
 
 
-def _check_tests_counter(gc, oc, b, efS):
+def _check_tests_counter(gix, q, K, efS, gc, oc, search_b=0):
     """`tests` counts the neighbours the projection test was evaluated for.  Short searches (exact LDS seen
     set) evaluate it for unseen neighbours only, like the oracle.  Long searches consult the second level of
-    the seen set only for neighbours that pass, so their count also holds seen neighbours that the first
-    level did not recognise: an upper bound of the oracle's."""
+    the seen set only for neighbours that pass, so their count also holds the seen neighbours that the first
+    level did not recognise and that failed the test: at most one per exact distance computed and expanded
+    node (a seen node is met again through one of its in-edges).  In counting mode
+    (PAG_FLAG_EXACT_TEST_COUNT) the second level is consulted first and the count is the oracle's."""
+    from paper_2603_06660_amd import FLAG_EXACT_TEST_COUNT
+    b = search_b if search_b else max(10, K)
     if b + 8 * max(efS, b) <= 1024:
         assert gc["tests"] == oc["tests"], (gc["tests"], oc["tests"])
-    else:
-        assert oc["tests"] <= gc["tests"] <= 64 * gc["hops"], (gc["tests"], oc["tests"])
+        return
+    assert oc["tests"] <= gc["tests"], (gc["tests"], oc["tests"])
+    qd = torch.from_numpy(q).cuda()
+    ref = gix.search(qd, K, efS)
+    try:
+        gix.set_search_options(search_b, FLAG_EXACT_TEST_COUNT)
+        gix.reset_counters()
+        got = gix.search(qd, K, efS)
+        gx = gix.counters()
+    finally:
+        gix.set_search_options(search_b, 0)
+    assert torch.equal(ref[0], got[0]) and torch.equal(ref[1], got[1])
+    assert gx["tests"] == oc["tests"], (gx["tests"], oc["tests"])
+    for k_g, k_o in (("hops", "hops"), ("passes", "passes"), ("exact", "exact"), ("rounds", "rounds")):
+        assert gx[k_g] == oc[k_o], (k_g, gx[k_g], oc[k_o])
 
 
 @pytest.fixture(scope="module")
@@ -127,7 +144,7 @@ def test_search_parity_config1(orc, cfg1_small, cfg1_oracle_index, imported, efS
     for k_g, k_o in (("hops", "hops"), ("passes", "passes"), ("exact", "exact"),
                      ("rounds", "rounds"), ("rf_overflow", "rf_over"), ("rt_overflow", "rt_over")):
         assert abs(gc[k_g] - oc[k_o]) <= 0.002 * max(1, oc[k_o]), (k_g, gc[k_g], oc[k_o])
-    _check_tests_counter(gc, oc, max(10, w.K), efS)
+    _check_tests_counter(imported, q, w.K, efS, gc, oc)
 
 
 def test_search_is_deterministic(cfg1_small, imported):
@@ -175,7 +192,7 @@ def test_large_working_sets(orc, cfg1_small, cfg1_oracle_index, imported, K, efS
         for k_g, k_o in (("hops", "hops"), ("passes", "passes"), ("exact", "exact"),
                          ("rounds", "rounds"), ("rf_overflow", "rf_over"), ("rt_overflow", "rt_over")):
             assert gc[k_g] == oc[k_o], (k_g, gc[k_g], oc[k_o])
-        _check_tests_counter(gc, oc, b if b else max(10, K), efS)
+        _check_tests_counter(imported, q[:48], K, efS, gc, oc, search_b=b)
     finally:
         imported.set_search_options(0, 0)
 
