@@ -157,6 +157,23 @@ int pag_search(const pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uin
                int64_t* ids, float* dists);
 
 /*
+ * pag_search_static: pag_search for callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results.  It calls
+ * no hipMalloc, hipFree or other allocating routine: its workspaces (rotated queries, projection tables,
+ * normalised copies, per-wave seen-set bitmaps) live in one 48 MB device array that is part of the library
+ * and that every GPU the library runs on holds until the process ends (its address on a GPU is looked up
+ * when an index is created there, so the call itself loads nothing either).  Limits (PAG_EUNSUPPORTED beyond
+ * them, nothing is launched): nq * (d + 16 * S [+ d for PAG_COS]) <= 4,194,304 floats, where S is
+ * num_subspaces rounded up to 16, 32 or 64; index capacity <= 4,194,304 vectors; working set b <= 128
+ * (K <= 128).  With fewer bitmaps than the GPU could keep waves busy the call is slower than pag_search,
+ * never different.  All calls on one GPU share the array: calls that overlap in time on one GPU (from
+ * any thread, on any index) race and must be serialised by the caller.  The call synchronises the
+ * index's stream before it returns, like pag_search.
+ */
+int pag_search_static(const pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uint32_t efS,
+                      int64_t* ids, float* dists);
+
+/*
  * pag_insert (online insertion, Sec. 4.1): appends the m vectors X (dev,
  * float32 [m*d]); they receive ids n .. n+m-1 and are linked in shuffled
  * batches like the vectors of pag_build.  The vectors of one batch do not see

@@ -18,7 +18,7 @@ FLAG_EXACT_TEST_COUNT = 16
 _METRICS = {"l2": L2, "ip": IP, "cos": COS, "cosine": COS, L2: L2, IP: IP, COS: COS}
 
 EXPORTED_SYMBOLS = (
-    "pag_build", "pag_search", "pag_insert", "pag_free", "pag_describe", "pag_export", "pag_import",
+    "pag_build", "pag_search", "pag_search_static", "pag_insert", "pag_free", "pag_describe", "pag_export", "pag_import",
     "pag_get_counters", "pag_reset_counters", "pag_set_search_options", "pag_set_seen_capacity_log2",
     "pag_prepare_queries", "pag_exact_distances", "pag_screen", "pag_edge_info", "pag_insertion_candidates",
     "pag_measure_row_reads",
@@ -172,6 +172,15 @@ class PagIndex:
         _check(load_library().pag_search(self._h, _dev_f32(queries, "queries"), C.c_uint64(nq), C.c_uint32(K),
                                          C.c_uint32(efS), C.c_void_p(ids.data_ptr()), C.c_void_p(dists.data_ptr())),
                "pag_search")
+        return ids, dists
+
+    def search_static(self, queries, K, efS, out):
+        """pag_search_static: the search without any allocation; `out` = (ids, dists) preallocated on the device."""
+        ids, dists = out
+        nq = queries.shape[0]
+        _check(load_library().pag_search_static(self._h, _dev_f32(queries, "queries"), C.c_uint64(nq), C.c_uint32(K),
+                                                C.c_uint32(efS), C.c_void_p(ids.data_ptr()),
+                                                C.c_void_p(dists.data_ptr())), "pag_search_static")
         return ids, dists
 
     def insert(self, X):

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstring>
 #include <functional>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -188,6 +189,35 @@ struct DeviceGuard {
     ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
 };
 
+}  // namespace
+
+// The workspace of pag_search_static: one file-scope device array.  Each GPU the library runs on holds its own copy,
+// at its own address, until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the device address is looked up once per device, with that device current, and used from
+// then on.
+static __device__ __align__(256) unsigned char scratch[PAG_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices];        // device address of `scratch` per device, null until looked up
+
+int scratch_of(int device, unsigned char** out) {
+    PAG_CHECK(device >= 0 && device < kMaxDevices, PAG_EUNSUPPORTED, "pag_search_static: device number above 63");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        PAG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));      // the current device's copy
+        PAG_CHECK(p != nullptr, PAG_EHIP, "pag_search_static: the scratch array has no device address");
+        g_scratch_ptr[device] = (unsigned char*)p;
+    }
+    *out = g_scratch_ptr[device];
+    return PAG_OK;
+}
+}  // namespace
+
+namespace {
+
 // allocate the HBM-resident parts of an index for `capacity` nodes
 int alloc_index(pag_index* ix) {
     int rc;
@@ -205,7 +235,9 @@ int alloc_index(pag_index* ix) {
     if ((rc = dev_alloc(&ix->d_counters, CTR_COUNT))) return rc;
     PAG_HIP(hipMemsetAsync(ix->d_counters, 0, CTR_COUNT * sizeof(u64), ix->stream));
     for (auto& e : ix->ev) PAG_HIP(hipEventCreate(&e));
-    return PAG_OK;
+    // pag_search_static must find its workspace without loading or allocating anything: look it up now
+    unsigned char* static_ws = nullptr;
+    return scratch_of(ix->device, &static_ws);
 }
 
 pag_index* new_index(const pag_params* p, uint32_t d) {
@@ -674,6 +706,70 @@ extern "C" int pag_search(const pag_index* cix, const float* Q, uint64_t nq, uin
     pag_index* ix = const_cast<pag_index*>(cix);   // workspaces and counters are mutable state of the handle
     PAG_CHECK(ix != nullptr, PAG_EINVAL, "index is null");
     return search_impl(ix, Q, nq, K, efS, ids, dists);
+}
+
+// ---------------------------------------------------------------------------------------------
+// pag_search_static: pag_search for callers that cannot allocate.  Everything the search needs beyond the index, the
+// queries and the outputs -- rotated queries, projection tables, normalised copies (COS) and the per-wave seen-set
+// bitmaps -- lives in one file-scope device array.  Each GPU holds its own copy of that array, at its own address,
+// until the process ends; the address is looked up once per device.
+extern "C" int pag_search_static(const pag_index* cix, const float* Q, uint64_t nq, uint32_t K, uint32_t efS,
+                                 int64_t* ids, float* dists) {
+    pag_index* ix = const_cast<pag_index*>(cix);
+    PAG_CHECK(ix != nullptr, PAG_EINVAL, "index is null");
+    if (nq == 0) return PAG_OK;
+    PAG_CHECK(Q && ids && dists, PAG_EINVAL, "Q, ids or dists is null");
+    PAG_CHECK(K >= 1 && K <= ix->n, PAG_EINVAL, "K must be in 1..n");
+    PAG_CHECK(efS >= 1, PAG_EINVAL, "efS must be >= 1");
+    const u32 b = ix->search_b ? ix->search_b : std::max<u32>(10, K);
+    PAG_CHECK(b >= K, PAG_EINVAL, "search_b must be >= K");
+    PAG_CHECK(b <= PAG_LDS_RING_MAX_B, PAG_EUNSUPPORTED,
+              "pag_search_static: working sets above 128 nodes (K > 128) keep their rings in a workspace; use pag_search");
+    DeviceGuard g(ix->device);
+    const pag_layout& L = ix->L;
+    // query part: rotated queries, tables, normalised copies; each block starts on a 256-byte boundary
+    const u64 per_query = (u64)L.d + (u64)L.Ppad * PAG_NCODE + (ix->metric == PAG_COS ? L.d : 0);
+    PAG_CHECK(nq <= PAG_STATIC_QUERY_FLOATS / per_query, PAG_EUNSUPPORTED,
+              "pag_search_static: nq * (d + 16 * subspaces [+ d for cosine]) exceeds 4,194,304 floats; split the batch or use pag_search");
+    auto align256 = [](u64 x) { return (x + 255) / 256 * 256; };
+    const u64 off_qrot = 0;
+    const u64 off_tab = align256(off_qrot + nq * L.d * 4);
+    const u64 off_norm = align256(off_tab + nq * L.Ppad * PAG_NCODE * 4);
+    const u64 off_bitmap = align256(off_norm + (ix->metric == PAG_COS ? nq * L.d * 4 : 0));
+    int rc;
+    SearchArgs a;
+    u32 lds = 0;
+    int grid = 0;
+    if ((rc = search_plan(ix, b, efS, ix->n, &a, &lds, &grid))) return rc;
+    // bitmap part: as many per-wave bitmaps as fit behind the query part; fewer waves than the GPU could hold
+    // make the search slower, not different
+    const u64 room = (u64)PAG_STATIC_SCRATCH_BYTES - off_bitmap;
+    const u64 fit = room / (a.bitmap_words * 4);
+    PAG_CHECK(fit >= 64, PAG_EUNSUPPORTED,
+              "pag_search_static: the index capacity is too large for the static seen-set bitmaps (4,194,304 vectors at most); use pag_search");
+    if ((u64)grid > fit) grid = (int)fit;
+    if ((u64)grid > nq) grid = (int)nq;
+    unsigned char* base = nullptr;
+    if ((rc = scratch_of(ix->device, &base))) return rc;
+    a.qrot = (const float*)(base + off_qrot);
+    a.tables = (const float*)(base + off_tab);
+    a.bitmap = (u32*)(base + off_bitmap);
+    a.nq = (u32)nq; a.K = K;
+    a.out_ids = (long long*)ids; a.out_dists = dists;
+    a.out_scale = ix->metric == PAG_L2 ? 1.0f : 0.5f;
+    PAG_HIP(hipEventRecord(ix->ev[0], ix->stream));
+    // the array keeps whatever the last call left there, possibly under another layout: the bitmaps start clean
+    if ((rc = pag_launch_zero_u32(ix->stream, a.bitmap, (u64)grid * a.bitmap_words))) return rc;
+    if ((rc = prepare_into(ix, Q, nq, (float*)(base + off_norm), (float*)(base + off_qrot), (float*)(base + off_tab)))) return rc;
+    if ((rc = pag_launch_zero_u32(ix->stream, ix->d_qcounter, 1))) return rc;
+    PAG_HIP(hipEventRecord(ix->ev[1], ix->stream));
+    if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
+    PAG_HIP(hipEventRecord(ix->ev[2], ix->stream));
+    PAG_HIP(hipStreamSynchronize(ix->stream));
+    float ms = 0.f;
+    PAG_HIP(hipEventElapsedTime(&ms, ix->ev[0], ix->ev[1])); ix->last_prepare_ms = ms;
+    PAG_HIP(hipEventElapsedTime(&ms, ix->ev[1], ix->ev[2])); ix->last_search_ms = ms;
+    return PAG_OK;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -20,6 +20,8 @@ typedef uint32_t u32;
 #define PAG_LDS_RING_MAX_B 128  // larger working sets keep R_F / R_T in HBM (the kernel's NW > 2 instantiations)
 #define PAG_MAX_DEG 64      // one neighbour per lane
 #define PAG_MAX_CW 8        // code dwords per neighbour: up to 64 subspaces
+#define PAG_STATIC_SCRATCH_BYTES (48u << 20)   // the device array behind pag_search_static, per GPU
+#define PAG_STATIC_QUERY_FLOATS (4ull << 20)    // of which at most 16 MB hold rotated queries, tables and normalised copies
 
 void pag_set_error(const std::string& msg);
 

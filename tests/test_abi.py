@@ -66,6 +66,8 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.pag_searcher_create(None, None, C.byref(s)) == -1 and not s.value
     assert lib.pag_searcher_search(None, None, C.c_uint64(1), C.c_uint32(1), C.c_uint32(1), None, None) == -1
     assert lib.pag_searcher_free(None) == 0
+    assert lib.pag_search_static(None, None, C.c_uint64(1), C.c_uint32(1), C.c_uint32(1), None, None) == -1
+    assert b"null" in lib.pag_last_error()
     assert lib.pag_insertion_candidates(None, None, C.c_uint64(1), None, None, None, None, None, None) == -1
 
 
