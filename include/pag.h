@@ -108,7 +108,8 @@ typedef struct {
     uint32_t* entry;     /* host [n_entry]    entry node ids; a search starts from the first b of them */
 } pag_arrays;
 
-/* Sums over all pag_search calls since creation or the last pag_reset_counters (Sec. 4.2's quantities). */
+/* Sums over all searches since creation or the last pag_reset_counters (Sec. 4.2's quantities); the searches
+ * that pag_build and pag_insert run for their own vectors count as well. */
 typedef struct {
     uint32_t struct_size;
     uint32_t adj_record_bytes;   /* size of one node's adjacency record in HBM */
@@ -131,6 +132,9 @@ typedef struct {
                                        all zero unless the library was compiled with -DPAG_PHASE_TIMERS */
     uint64_t relinked_batches;      /* insertion batches, since the index was created, that were found to crowd a
                                        region of their own and were linked a second time (see pag_insert) */
+    double   last_build_phase_ms[4]; /* HIP-event times of the last pag_build / pag_insert, summed over its batches:
+                                       [0] the search kernel in indexing mode, [1] candidate sort + RobustPrune,
+                                       [2] pair sort + reverse edges and PES verification, [3] inference information */
 } pag_counters;
 
 /*

@@ -51,7 +51,8 @@ class _Counters(C.Structure):
                [(k, C.c_uint64) for k in ("queries", "hops", "tests", "passes", "exact", "rounds",
                                           "rf_overflow", "rt_overflow", "seen_spills")] + \
                [("last_search_kernel_ms", C.c_double), ("last_prepare_ms", C.c_double),
-                ("last_build_ms", C.c_double), ("phase_cycles", C.c_uint64 * 6), ("relinked_batches", C.c_uint64)]
+                ("last_build_ms", C.c_double), ("phase_cycles", C.c_uint64 * 6), ("relinked_batches", C.c_uint64),
+                ("last_build_phase_ms", C.c_double * 4)]
 
 
 _lib = None
@@ -214,8 +215,9 @@ class PagIndex:
     def counters(self):
         c = _Counters(C.sizeof(_Counters))
         _check(load_library().pag_get_counters(self._h, C.byref(c)), "pag_get_counters")
-        out = {k: getattr(c, k) for k, _ in c._fields_ if k not in ("struct_size", "phase_cycles")}
+        out = {k: getattr(c, k) for k, _ in c._fields_ if k not in ("struct_size", "phase_cycles", "last_build_phase_ms")}
         out["phase_cycles"] = list(c.phase_cycles)
+        out["last_build_phase_ms"] = list(c.last_build_phase_ms)
         return out
 
     def reset_counters(self):
@@ -324,8 +326,9 @@ class PagSearcher:
     def counters(self):
         c = _Counters(C.sizeof(_Counters))
         _check(load_library().pag_searcher_get_counters(self._h, C.byref(c)), "pag_searcher_get_counters")
-        out = {k: getattr(c, k) for k, _ in c._fields_ if k not in ("struct_size", "phase_cycles")}
+        out = {k: getattr(c, k) for k, _ in c._fields_ if k not in ("struct_size", "phase_cycles", "last_build_phase_ms")}
         out["phase_cycles"] = list(c.phase_cycles)
+        out["last_build_phase_ms"] = list(c.last_build_phase_ms)
         return out
 
     def close(self):

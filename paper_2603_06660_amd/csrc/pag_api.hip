@@ -535,6 +535,7 @@ extern "C" int pag_get_counters(const pag_index* ix, pag_counters* out) {
     out->last_build_ms = ix->last_build_ms;
     for (int i = 0; i < 6; ++i) out->phase_cycles[i] = h[CTR_PHASE0 + i];
     out->relinked_batches = ix->relinked_batches;
+    for (int i = 0; i < 4; ++i) out->last_build_phase_ms[i] = ix->build_phase_ms[i];
     return PAG_OK;
 }
 

@@ -408,7 +408,9 @@ struct BuildWs {
     void* sort_tmp = nullptr; size_t sort_bytes = 0;
     int *seg_begin = nullptr, *seg_end = nullptr;
     void* seg_tmp = nullptr; size_t seg_bytes = 0;
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};   // phase marks of one linking pass
     ~BuildWs() {
+        for (auto& e : ev) if (e) (void)hipEventDestroy(e);
         void* p[] = { cand, cand_sorted, cand_cnt, pes, rk_in, rk_out, rv_in, rv_out, edges, n_edges, order, density, sort_tmp, seg_begin, seg_end, seg_tmp };
         for (void* x : p) if (x) (void)hipFree(x);
     }
@@ -454,7 +456,9 @@ static int search_candidates(pag_index* ix, BuildWs& ws, const float* qrot, u64 
     a.cand = ws.cand; a.cand_cnt = ws.cand_cnt; a.cand_cap = cand_cap;
     a.pes = ws.pes;
     if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
+    if (ws.ev[0]) PAG_HIP(hipEventRecord(ws.ev[0], s));
     if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
+    if (ws.ev[1]) PAG_HIP(hipEventRecord(ws.ev[1], s));
     hipLaunchKernelGGL(k_cand_segments, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, ws.cand_cnt, (u32)m, cand_cap,
                        ws.seg_begin, ws.seg_end);
     PAG_HIP(hipGetLastError());
@@ -490,6 +494,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     if (n_end <= n_begin) return PAG_OK;
     const pag_layout& L = ix->L;
     hipStream_t s = ix->stream;
+    for (double& ms : ix->build_phase_ms) ms = 0.0;
     const u32 b = std::min<u32>(ix->efC, 100);
     const u32 Rmax = std::max<u32>(1, (ix->efC + b - 1) / b);
     const u32 cand_cap = Rmax * b;
@@ -535,6 +540,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
     max_batch = std::min<u64>(max_batch, count);       // a small insertion gets small workspaces
     const bool use_pes = !(ix->flags & PAG_FLAG_NO_PES);
     if ((rc = alloc_candidate_ws(ws, max_batch, cand_cap, L.deg, use_pes, s))) return rc;
+    for (auto& e : ws.ev) PAG_HIP(hipEventCreate(&e));
     const u64 max_pairs = max_batch * L.deg * (use_pes ? 2 : 1);
     PAG_ALLOC(ws.rk_in, max_pairs * 8);
     PAG_ALLOC(ws.rk_out, max_pairs * 8);
@@ -567,6 +573,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
                                ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ix->e2, ws.rk_in, ws.rv_in);
             PAG_HIP(hipGetLastError());
         }
+        PAG_HIP(hipEventRecord(ws.ev[2], s));
         // 4. group reverse pairs by target
         const u32 n_pairs = (u32)(m * L.deg * (use_pes ? 2 : 1));
         PAG_HIP(hipcub::DeviceRadixSort::SortPairs(ws.sort_tmp, ws.sort_bytes, ws.rk_in, ws.rk_out, ws.rv_in, ws.rv_out,
@@ -576,11 +583,18 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         hipLaunchKernelGGL(k_reverse, dim3(n_pairs), dim3(64), L.d * 4, s, pag_vecs_of(ix), ix->rec, ix->e2, L, ws.rk_out,
                            ws.rv_out, n_pairs, ws.edges, ws.n_edges);
         PAG_HIP(hipGetLastError());
+        PAG_HIP(hipEventRecord(ws.ev[3], s));
         // 6. inference information of the new forward edges and of every changed reverse slot
         if ((rc = pag_launch_edge_info_of(s, ix, nodes, m))) return rc;
+        PAG_HIP(hipEventRecord(ws.ev[4], s));
         u32 n_edges = 0;
         PAG_HIP(hipMemcpyAsync(&n_edges, ws.n_edges, 4, hipMemcpyDeviceToHost, s));
         PAG_HIP(hipStreamSynchronize(s));
+        for (int i = 0; i < 4; ++i) {            // search kernel | sort + RobustPrune | pair sort + reverse edges | inference information
+            float ms = 0.f;
+            PAG_HIP(hipEventElapsedTime(&ms, ws.ev[i], ws.ev[i + 1]));
+            ix->build_phase_ms[i] += ms;
+        }
         return pag_launch_edge_info_list(s, ix, ws.edges, n_edges);
     };
     while (done < count) {

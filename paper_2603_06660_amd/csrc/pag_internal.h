@@ -103,6 +103,7 @@ struct pag_index {
     hipEvent_t ev[4];
     int num_cu;
     double last_search_ms, last_prepare_ms, last_build_ms;
+    double build_phase_ms[4];             // of the last pag_build / pag_insert: search kernel, sort + RobustPrune, pair sort + reverse edges, inference information
     u64 relinked_batches;                 // insertion batches that were linked a second time (crowded regions)
     u32 insert_failed;                    // a pag_insert stopped half way: the index answers searches but takes no more vectors
 };
