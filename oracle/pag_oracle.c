@@ -489,19 +489,25 @@ int orc_prepare_queries(const orc_index *ix, int metric, const float *Q, uint64_
  * unless an already kept s has ||s-c|| <= ||v-c|| (then v can reach c through
  * s).  Stops at max_keep; no backfill.  Returns the number kept.
  */
-uint32_t orc_robust_prune(const orc_index *ix, uint32_t n_cand, const uint32_t *cand,
-                          const float *cand_key, uint32_t max_keep, uint32_t *kept,
-                          float *kept_key) {
+static uint32_t robust_prune_of(const orc_index *ix, uint32_t self, uint32_t n_cand, const uint32_t *cand,
+                                const float *cand_key, uint32_t max_keep, uint32_t *kept,
+                                float *kept_key) {
     const uint32_t d = ix->d;
     uint32_t nk = 0;
     for (uint32_t i = 0; i < n_cand && nk < max_keep; ++i) {
         const float *cv = ix->vec + (uint64_t)cand[i] * d;
-        int occluded = 0;
+        int occluded = cand[i] == self;      /* a node that is in the graph already finds itself: never its own neighbour */
         for (uint32_t s = 0; s < nk && !occluded; ++s)
             if (orc_key(d, ix->vec + (uint64_t)kept[s] * d, cv) <= cand_key[i]) occluded = 1;
         if (!occluded) { kept[nk] = cand[i]; kept_key[nk] = cand_key[i]; nk++; }
     }
     return nk;
+}
+
+uint32_t orc_robust_prune(const orc_index *ix, uint32_t n_cand, const uint32_t *cand,
+                          const float *cand_key, uint32_t max_keep, uint32_t *kept,
+                          float *kept_key) {
+    return robust_prune_of(ix, ORC_EMPTY, n_cand, cand, cand_key, max_keep, kept, kept_key);
 }
 
 static void write_edge(orc_index *ix, uint32_t u, uint32_t slot, uint32_t w) {
@@ -715,6 +721,13 @@ int orc_build(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, orc
  * edges, then the PES candidates, each group ascending by distance (ties: by position of the
  * source in the batch, then by its slot).  With max_batch == 1 this is the sequential
  * construction with the PES buffers verified after every insertion.
+ * What a sequential insertion has and a batch lacks is the sight of its batch-mates.  A batch found to
+ * crowd a region of its own (batch_is_crowded below: vectors inserted where the graph has none yet) is
+ * therefore linked a second time once its nodes are in the graph, in eight parts taken one after the other
+ * (what one part links is there for the next): each node searches again (and finds itself, which RobustPrune
+ * skips), its out-list is replaced by the new RobustPrune result, and the reverse edges and PES candidates
+ * are applied as before.  relink == 0 leaves the second pass out (to show what
+ * it is worth).
  */
 typedef struct { uint32_t target, pes, src; float dist; uint64_t seq; } rev_pair;
 
@@ -727,8 +740,38 @@ static int pair_cmp(const void *px, const void *py) {
     return 0;
 }
 
+/*
+ * Is a batch a region of its own?  (Batch-synchronous construction only; a sequential insertion sees
+ * every earlier node and needs no such rule.)  For 128 nodes x of the batch [v0, v0 + m), spread evenly,
+ * count among n_probe = min(m, v0, 2048) batch-mates and as many older nodes, both spread evenly, those
+ * that lie closer to x than the farthest out-neighbour x has just been given.  In a batch that is mixed
+ * like the graph the two counts agree; the batch is "crowded" when the mates number at least 32 and more
+ * than four times the older nodes.
+ */
+static int batch_is_crowded(const orc_index *ix, uint64_t v0, uint64_t m) {
+    const uint32_t d = ix->d, deg = ix->deg;
+    const uint64_t n_sample = 128;
+    uint64_t n_probe = m < v0 ? m : v0;
+    if (n_probe > 2048) n_probe = 2048;
+    uint64_t mates = 0, older = 0;
+    for (uint64_t i = 0; i < n_sample; ++i) {
+        const uint64_t x = v0 + i * m / n_sample;
+        const float *xv = ix->vec + x * d;
+        float far = 0.0f;
+        for (uint32_t s = 0; s < deg; ++s)
+            if (ix->adj[x * deg + s] != ORC_EMPTY && ix->e2[x * deg + s] > far) far = ix->e2[x * deg + s];
+        for (uint64_t j = 0; j < n_probe; ++j) {
+            const uint64_t y = v0 + j * m / n_probe, o = j * v0 / n_probe;
+            if (y != x && orc_key(d, xv, ix->vec + y * d) < far) mates++;
+            if (orc_key(d, xv, ix->vec + o * d) < far) older++;
+        }
+    }
+    return mates >= 32 && (double)mates > 4.0 * (double)(older > 1 ? older : 1);
+}
+
 int orc_build_batched(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_end, uint64_t max_batch,
-                      int use_pes, orc_counters *ctr, uint64_t *pes_added, uint64_t *n_batches) {
+                      int use_pes, int relink, orc_counters *ctr, uint64_t *pes_added, uint64_t *n_batches,
+                      uint64_t *n_relinked) {
     const uint32_t d = ix->d, P = ix->P, deg = ix->deg;
     uint32_t b = efC < 100 ? efC : 100;
     if (b == 0 || d % P != 0 || max_batch == 0) return -1;
@@ -746,7 +789,7 @@ int orc_build_batched(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_
     uint32_t *kept = (uint32_t *)malloc(sizeof(uint32_t) * deg);
     float *kkey = (float *)malloc(sizeof(float) * deg);
     rev_pair *pairs = (rev_pair *)malloc(sizeof(rev_pair) * 2 * (size_t)deg * max_batch);
-    uint64_t v0 = n_start, added = 0, batches = 0;
+    uint64_t v0 = n_start, added = 0, batches = 0, relinked = 0;
     if (n_start == 0) {
         uint64_t n_init = n_end < b ? n_end : b;
         init_nodes(ix, n_init);
@@ -758,50 +801,63 @@ int orc_build_batched(orc_index *ix, uint32_t efC, uint64_t n_start, uint64_t n_
         if (m > max_batch) m = max_batch;
         const uint64_t half = graph / 2 ? graph / 2 : 1;
         if (m > half) m = half;
-        /* 1. every node of the batch searches the graph of before the batch */
-        for (uint64_t j = 0; j < m; ++j) {
-            const float *vv = ix->vec + (v0 + j) * d;
-            orc_table(d, P, ix->cb, vv, T, NULL);
-            nHb[j] = 0;
-            orc_search_core(ix, graph, vv, T, efC, b, efC, 0, &sc, rl + j * rl_room, &n_rl[j], &local,
-                            use_pes ? Hb + j * deg : NULL, use_pes ? &nHb[j] : NULL, deg);
-        }
-        /* 2. RobustPrune -> N_out(v); the reverse edges and PES candidates are collected */
-        uint64_t np = 0;
-        for (int pes = 0; pes <= (use_pes ? 1 : 0); ++pes)
-            for (uint64_t j = 0; j < m; ++j) {
-                const uint32_t v = (uint32_t)(v0 + j);
-                if (!pes) {
-                    const ent *r = rl + j * rl_room;
-                    for (uint32_t i = 0; i < n_rl[j]; ++i) { cand[i] = r[i].id; ckey[i] = r[i].dist; }
-                    uint32_t nk = orc_robust_prune(ix, n_rl[j], cand, ckey, deg, kept, kkey);
-                    for (uint32_t i = 0; i < nk; ++i) {
-                        write_edge(ix, v, i, kept[i]);
-                        rev_pair p = { kept[i], 0, v, kkey[i], np };
-                        pairs[np++] = p;
-                    }
-                } else {
-                    for (uint32_t i = 0; i < nHb[j]; ++i) {
-                        const ent h = Hb[j * deg + i];
-                        int dup = h.id == v;             /* already an out-neighbour of v: it has its reverse edge */
-                        for (uint32_t s = 0; s < deg; ++s) if (ix->adj[(uint64_t)v * deg + s] == h.id) dup = 1;
-                        if (dup) continue;
-                        rev_pair p = { h.id, 1, v, h.dist, np };
-                        pairs[np++] = p;
+        /* one linking pass over the batch; a crowded batch gets a second one, in which its nodes are part of the
+         * graph, taken in eight parts one after the other (so that what one part links is there for the next) */
+        const uint64_t parts = 8;
+        for (uint64_t pass = 0; pass <= parts; ++pass) {
+            const uint64_t visible = pass == 0 ? graph : graph + m;
+            const uint64_t j0 = pass == 0 ? 0 : m * (pass - 1) / parts, j1 = pass == 0 ? m : m * pass / parts;
+            /* 1. every node of the pass searches the graph as it is before the pass */
+            for (uint64_t j = j0; j < j1; ++j) {
+                const float *vv = ix->vec + (v0 + j) * d;
+                orc_table(d, P, ix->cb, vv, T, NULL);
+                nHb[j] = 0;
+                orc_search_core(ix, visible, vv, T, efC, b, efC, 0, &sc, rl + j * rl_room, &n_rl[j], &local,
+                                use_pes ? Hb + j * deg : NULL, use_pes ? &nHb[j] : NULL, deg);
+            }
+            /* 2. RobustPrune -> N_out(v), replacing what v had; the reverse edges and PES candidates are collected */
+            uint64_t np = 0;
+            for (int pes = 0; pes <= (use_pes ? 1 : 0); ++pes)
+                for (uint64_t j = j0; j < j1; ++j) {
+                    const uint32_t v = (uint32_t)(v0 + j);
+                    if (!pes) {
+                        const ent *r = rl + j * rl_room;
+                        for (uint32_t i = 0; i < n_rl[j]; ++i) { cand[i] = r[i].id; ckey[i] = r[i].dist; }
+                        uint32_t nk = robust_prune_of(ix, v, n_rl[j], cand, ckey, deg, kept, kkey);
+                        for (uint32_t i = 0; i < deg; ++i) clear_edge(ix, v, i);
+                        for (uint32_t i = 0; i < nk; ++i) {
+                            write_edge(ix, v, i, kept[i]);
+                            rev_pair p = { kept[i], 0, v, kkey[i], np };
+                            pairs[np++] = p;
+                        }
+                    } else {
+                        for (uint32_t i = 0; i < nHb[j]; ++i) {
+                            const ent h = Hb[j * deg + i];
+                            int dup = h.id == v;             /* already an out-neighbour of v: it has its reverse edge */
+                            for (uint32_t s = 0; s < deg; ++s) if (ix->adj[(uint64_t)v * deg + s] == h.id) dup = 1;
+                            if (dup) continue;
+                            rev_pair p = { h.id, 1, v, h.dist, np };
+                            pairs[np++] = p;
+                        }
                     }
                 }
+            /* 3. applied target by target (an edge that exists already is left alone) */
+            qsort(pairs, np, sizeof(rev_pair), pair_cmp);
+            for (uint64_t i = 0; i < np; ++i) {
+                if (pairs[i].pes) added += (uint64_t)orc_pes_edge(ix, pairs[i].target, pairs[i].src, pairs[i].dist);
+                else orc_reverse_edge(ix, pairs[i].target, pairs[i].src, pairs[i].dist);
             }
-        /* 3. applied target by target */
-        qsort(pairs, np, sizeof(rev_pair), pair_cmp);
-        for (uint64_t i = 0; i < np; ++i) {
-            if (pairs[i].pes) added += (uint64_t)orc_pes_edge(ix, pairs[i].target, pairs[i].src, pairs[i].dist);
-            else orc_reverse_edge(ix, pairs[i].target, pairs[i].src, pairs[i].dist);
+            if (pass == 0) {
+                if (!relink || m < 64 || graph < 64 || !batch_is_crowded(ix, v0, m)) break;
+                relinked++;
+            }
         }
         v0 += m;
         batches++;
     }
     if (pes_added) *pes_added = added;
     if (n_batches) *n_batches = batches;
+    if (n_relinked) *n_relinked = relinked;
     if (ctr) *ctr = local;
     free(sc.seen); free(sc.seen_list); free(T); free(rl); free(n_rl); free(Hb); free(nHb);
     free(cand); free(ckey); free(kept); free(kkey); free(pairs);

@@ -227,17 +227,18 @@ class OracleIndex:
             vec = vec.astype(np.float16).astype(np.float32)
         return vec
 
-    def _link(self, n_start, efC, pes, pes_every, max_batch):
+    def _link(self, n_start, efC, pes, pes_every, max_batch, relink=True):
         """Alg. 1 over the nodes [n_start, n): sequential (max_batch = 0) or batch-synchronous."""
         L = lib()
         ctr = Counters()
         st = self._struct()
         added = C.c_uint64(0)
         batches = C.c_uint64(0)
+        relinked = C.c_uint64(0)
         if max_batch:
             rc = L.orc_build_batched(C.byref(st), C.c_uint32(efC), C.c_uint64(n_start), C.c_uint64(self.n),
-                                     C.c_uint64(max_batch), C.c_int(1 if pes else 0), C.byref(ctr),
-                                     C.byref(added), C.byref(batches))
+                                     C.c_uint64(max_batch), C.c_int(1 if pes else 0), C.c_int(1 if relink else 0),
+                                     C.byref(ctr), C.byref(added), C.byref(batches), C.byref(relinked))
         else:
             rc = L.orc_build(C.byref(st), C.c_uint32(efC), C.c_uint64(n_start), C.c_uint64(self.n), C.byref(ctr),
                              C.c_int(1 if pes else 0), C.c_uint64(pes_every), C.byref(added))
@@ -245,6 +246,7 @@ class OracleIndex:
         self.build_counters = ctr.as_dict()
         self.pes_edges_added = int(added.value)
         self.batches = int(batches.value)
+        self.relinked_batches = int(relinked.value)
 
     @classmethod
     def build(cls, data, metric=L2, deg=32, P=16, efC=100, seed=1, rot=None, cb=None, pes=True, vec_f16=False,
@@ -267,7 +269,7 @@ class OracleIndex:
         self._link(0, efC, pes, pes_every, max_batch)
         return self
 
-    def insert(self, data, efC=100, pes=True, pes_every=0, max_batch=0, vec_f16=False):
+    def insert(self, data, efC=100, pes=True, pes_every=0, max_batch=0, vec_f16=False, relink=True):
         """Online insertion (Sec. 4.1): the rows of `data` are appended and linked like the nodes of build();
         the entry list grows with them until it holds 1024 nodes."""
         new = self._ingest(data, self.metric, self.rot, vec_f16)
@@ -281,7 +283,7 @@ class OracleIndex:
         if self.entry.size < 1024:
             grow = np.arange(n0, min(self.n, n0 + 1024 - self.entry.size), dtype=np.uint32)
             self.entry = np.ascontiguousarray(np.concatenate([self.entry, grow]))
-        self._link(n0, efC, pes, pes_every, max_batch)
+        self._link(n0, efC, pes, pes_every, max_batch, relink)
 
     def index_search(self, v_rot, efC, n_nodes=None):
         """The search of one insertion (Alg. 1) for the rotated point v over the nodes [0, n_nodes):

@@ -356,7 +356,8 @@ __global__ void __launch_bounds__(64) k_reverse(pag_vecs vec, uint8_t* __restric
 // the batch-mates and the older nodes of the graph (n_probe of each, spread evenly) that lie closer than the
 // farthest neighbour the node has just been given: added to out[2i] (mates) and out[2i+1] (older nodes).  In a batch drawn from
 // the same distribution as the graph the two fractions agree; where the batch-mates are many times denser (new
-// data inserted next to none of the old) the batch is linked a second time, now that its nodes are in the graph.
+// data inserted next to none of the old) the batch is linked a second time, now that its nodes are in the graph,
+// in eight parts taken one after the other.
 // order: the ids being inserted, in insertion order; the first `done` of them and all ids below n_begin are in the
 // graph already, the batch is order[done .. done + m).
 __global__ void __launch_bounds__(64) k_batch_density(pag_vecs vec, const uint8_t* __restrict__ recs, const float* __restrict__ e2,
@@ -622,7 +623,12 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
             // both counts are out of ns * np probes: their ratio compares the two densities directly
             const bool crowded = mates >= 32.0 && mates > kCrowdedRatio * std::max(older, 1.0);
             if (crowded) {
-                if ((rc = link(nodes, m))) return rc;
+                // in eight parts, one after the other: what one part links is there for the next
+                constexpr u64 kParts = 8;
+                for (u64 k = 0; k < kParts; ++k) {
+                    const u64 j0 = m * k / kParts, j1 = m * (k + 1) / kParts;
+                    if (j1 > j0 && (rc = link(nodes + j0, j1 - j0))) return rc;
+                }
                 ix->relinked_batches++;
             }
         }

@@ -210,3 +210,32 @@ def test_insertion_candidates(orc, cfg1_small, cfg1_oracle_index):
             n_pes += len(ohi)
         assert n_pes > 0
         gix.close()
+
+
+def test_crowded_insert(orc):
+    """pag_insert of vectors that all lie where the index has none yet (the points farthest along one
+    direction, held out of the build and inserted in order along it): the batch is found to crowd a region
+    of its own and is linked a second time, in eight parts.  Density rule, second pass and all, the graph
+    must be the oracle's."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_KEEP_ORDER
+    w = wl.workload(1, n=6000, nq=64)
+    base = wl.make(w, "base")
+    u = base[0] - base.mean(0)
+    proj = base @ (u / np.linalg.norm(u))
+    new = proj > np.quantile(proj, 0.88)
+    old_rows, new_rows = base[~new], base[new][np.argsort(proj[new], kind="stable")]
+    deg, P, efC = 32, 16, 64
+    rot = _signed_permutation(w.d, 5)
+    n_all = len(base)
+    oix = orc.OracleIndex.build(old_rows, wl.L2, deg=deg, P=P, efC=efC, rot=rot, seed=7, pes=True,
+                                max_batch=min(len(old_rows), 1024))
+    assert oix.relinked_batches == 0
+    gix = PagIndex.from_arrays(oix.vec, oix.adj, oix.a, oix.c, oix.e2, oix.codes, oix.rot, oix.cb, oix.entry,
+                               metric="l2", ef_construction=efC, capacity=n_all, flags=FLAG_KEEP_ORDER)
+    gix.insert(torch.from_numpy(new_rows).cuda())
+    oix.insert(new_rows, efC=efC, pes=True, max_batch=min(len(new_rows), 1024))
+    assert oix.relinked_batches == 1 and gix.counters()["relinked_batches"] == 1
+    ex = gix.export()
+    assert np.array_equal(ex["vectors"], oix.vec)
+    _assert_same_index(ex, oix, "crowded insert")

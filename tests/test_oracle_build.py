@@ -211,3 +211,48 @@ def test_batches_of_one_are_the_sequential_build(orc, cfg1_small):
     end = orc.OracleIndex.build(base[:n], w.metric, pes=True, **kw)
     assert 0 < (end.adj != seq.adj).mean() < 0.1
     assert abs(wl.recall_at_k(end.search(q, w.K, 32)[0], gt12) - r_seq) <= 0.02
+
+
+def _held_out_region(n, frac=0.12):
+    """cfg 1's mixture with the points farthest along one direction held out: (old rows, new rows sorted along
+    that direction).  Inserting the new rows puts them where the index built on the old rows has no node."""
+    w = wl.workload(1, n=n, nq=400)
+    base, q = wl.make(w, "base"), wl.make(w, "query")
+    u = base[0] - base.mean(0)
+    proj = base @ (u / np.linalg.norm(u))
+    cut = np.quantile(proj, 1.0 - frac)
+    new = proj > cut
+    return w, base[~new], base[new][np.argsort(proj[new], kind="stable")], q
+
+
+def test_crowded_batch_is_linked_twice(orc):
+    """Batch-synchronous insertion of vectors that all lie where the index has none yet: the batch's nodes do
+    not see each other in the first pass; the density rule notices and links them a second time, after which
+    queries that land in the new region are answered as well as by the sequential construction.  Ordinary
+    builds never trigger the rule."""
+    w, old, new, q = _held_out_region(4000)
+    kw = dict(deg=w.deg, P=w.P, efC=64, seed=19)
+    allv = np.concatenate([old, new])
+    gt, _ = wl.brute_force(allv, q, w.K)
+    near = gt[:, 0] >= len(old)
+    assert near.sum() >= 20 and 300 <= len(new) <= 600
+    seq = orc.OracleIndex.build(old, w.metric, pes=True, pes_every=1, **kw)
+    seq.insert(new, efC=64, pes=True, pes_every=1)
+    bat = orc.OracleIndex.build(old, w.metric, pes=True, max_batch=1024, **kw)
+    assert bat.relinked_batches == 0                       # a mixed build: batch-mates are as dense as older nodes
+    bat.insert(new, efC=64, pes=True, max_batch=len(new))
+    assert bat.batches == 1 and bat.relinked_batches == 1
+    once = orc.OracleIndex.build(old, w.metric, pes=True, max_batch=1024, **kw)
+    once.insert(new, efC=64, pes=True, max_batch=len(new), relink=False)        # what the rule is worth
+    r_seq = wl.recall_at_k(seq.search(q, w.K, 32)[0][near], gt[near])
+    r_bat = wl.recall_at_k(bat.search(q, w.K, 32)[0][near], gt[near])
+    r_once = wl.recall_at_k(once.search(q, w.K, 32)[0][near], gt[near])
+    assert r_bat >= r_seq - 0.05 and r_seq >= 0.9 and r_once <= r_bat - 0.2, (r_seq, r_bat, r_once)
+    # the relinked nodes link to each other: most of their out-neighbours are batch-mates
+    adj_new = bat.adj[len(old):]
+    used = adj_new != orc.EMPTY
+    assert (adj_new[used] >= len(old)).mean() > 0.5
+    # no node lists itself or a neighbour twice
+    for v in range(len(old), bat.n):
+        nb = bat.adj[v][bat.adj[v] != orc.EMPTY]
+        assert v not in nb and len(set(nb.tolist())) == len(nb)
