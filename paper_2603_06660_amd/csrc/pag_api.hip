@@ -658,7 +658,7 @@ int pag_search_common(pag_index* ix, u32 b, u32 ef, u64 n_limit, SearchArgs* a, 
     }
     a->bitmap = ix->ws_bitmap;
     if (b > PAG_LDS_RING_MAX_B) {
-        if ((rc = ensure_ws(&ix->ws_rings, &ix->ws_rings_cap, (u64)*grid * 2 * (a->ring_mask + 1)))) return rc;
+        if ((rc = ensure_ws(&ix->ws_rings, &ix->ws_rings_cap, (u64)*grid * 3 * (u64)(a->ring_mask + 1)))) return rc;
         a->rings = ix->ws_rings;
     }
     return PAG_OK;

@@ -97,7 +97,7 @@ struct pag_index {
     float* ws_tab;   u64 ws_tab_cap;      // floats
     float* ws_norm;  u64 ws_norm_cap;     // floats (normalised copies for COS)
     u32* ws_bitmap;  u64 ws_bitmap_cap;   // u32 words: per-wave seen-set spill bitmaps
-    u64* ws_rings;   u64 ws_rings_cap;    // u64 keys: per-wave R_F / R_T of large working sets
+    u64* ws_rings;   u64 ws_rings_cap;    // u64 keys: per-wave R_F / R_T / R_L of large working sets
     u32* d_qcounter;                      // persistent-wave work counter
     u64* d_counters;                      // CTR_COUNT
     hipEvent_t ev[4];
@@ -120,7 +120,7 @@ struct SearchArgs {
     u32 nq, K, b, Rmax, hlog, blog, flags;   // hlog: log2 slots of the LDS hash; blog: log2 bits of the Bloom filter (0 = none)
     u32 off_hash, off_bloom, off_sa, off_sb, off_rf, off_rt;   // LDS offsets (bytes)
     u32 ring_mask;           // rings live in power-of-two buffers of >= b slots; only the last b pushes are valid
-    u64* rings;              // [grid * 2 * (ring_mask + 1)] per-wave R_F, R_T when b > PAG_LDS_RING_MAX_B, else unused
+    u64* rings;              // [grid * 3 * (ring_mask + 1)] per-wave R_F, R_T and R_L when b > PAG_LDS_RING_MAX_B, else unused
     long long* out_ids;      // [nq * K]       (search mode)
     float* out_dists;        // [nq * K]
     float out_scale;         // 1 for L2, 0.5 for IP / COS

@@ -70,14 +70,10 @@ int pag_search_lds_bytes(const pag_layout& L, u32 b, u32 hlog, u32 blog, SearchA
     u32 off = align_up(L.Ppad * PAG_NCODE * 4, 16);
     a->off_hash = off; off += (4u << hlog);
     a->off_bloom = off; off += blog ? (1u << blog) / 8 : 0;
-    // round ends sort up to 2b keys: by ranks from SA into SB, or, for long lists, in place in SA
-    // padded to a power of two
+    // round ends sort up to 2b keys: working sets of up to 128 nodes by ranks from SA into SB, both in LDS;
+    // larger ones in registers (no LDS)
     u32 sa = 2 * b, sb = 2 * b;
-    if (2 * b > PAG_RANK_SORT_MAX) {
-        sa = 64;
-        while (sa < 2 * b) sa *= 2;
-        sb = 0;
-    }
+    if (b > PAG_LDS_RING_MAX_B) sa = sb = 0;
     a->off_sa = off;   off += align_up(sa * 8, 16);
     a->off_sb = off;   off += align_up(sb * 8, 16);
     u32 ring = 32;                                    // the last b pushes must stay apart: any power of two >= b

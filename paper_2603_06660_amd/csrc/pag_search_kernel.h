@@ -3,8 +3,10 @@
 //
 // Wave-level data placement (64 lanes):
 //   query        registers, NQ float4 per lane (element chunk c*64+lane)
-//   W            registers, sorted ascending by key; rank r lives in slot r/64 of lane r%64 (NW slots, b <= 64 NW)
-//   R_L          registers, same placement (capacity K <= b)
+//   W            registers, NW slots per lane (b <= 64 NW).  Up to 128 nodes (NW <= 2): sorted ascending by key, rank r
+//                in slot r/64 of lane r%64.  Above (NW >= 4): unsorted, entry i in slot i/64 of lane i%64; the node to
+//                expand and the farthest member are found by wave-wide minima / maxima, the farthest one is cached
+//   R_L          up to 128 nodes: registers, same placement (capacity K <= b); above: the front of a per-wave HBM buffer
 //   table T      LDS, float [Ppad][16]
 //   seen set     short searches: LDS open-addressing hash of node ids (exact; overflows into a
 //                per-wave HBM bitmap).  Long searches: every id goes to the per-wave HBM bitmap,
@@ -13,7 +15,8 @@
 //   R_F, R_T     rings (power-of-two buffers, the last b pushes are valid): LDS, or per-wave HBM
 //                buffers for working sets above 128 nodes, which are pushed to rarely and read
 //                once per round
-//   SA, SB       LDS scratch for scatters and sorts (SB only for working sets of up to 128 nodes)
+//   SA, SB       scratch for scatters and sorts: LDS for working sets of up to 128 nodes; above, two per-wave HBM buffers
+//                that are touched at round ends only (SA holds R_L in front and sorts R_L + W, SB sorts the rings)
 // A key packs (dist bits << 32) | (id << 1) | visited, so that unsigned comparison orders by
 // (dist, id); distances are sums of squares, hence non-negative and monotone as bit patterns.
 //
@@ -89,7 +92,7 @@ __device__ __forceinline__ void rank_sort(const u64* src, u64* dst, u32 n, int l
     }
 }
 
-// In-place ascending bitonic sort of S[0, n) by one wave; S has room for n rounded up to a power
+// In-place ascending bitonic sort of S[0, n) in LDS by one wave; S has room for n rounded up to a power
 // of two (the tail is padded with the largest key).
 __device__ __forceinline__ void bitonic_sort(u64* S, u32 n, int lane) {
     u32 N = 64;
@@ -106,6 +109,44 @@ __device__ __forceinline__ void bitonic_sort(u64* S, u32 n, int lane) {
             }
             lds_sync();
         }
+}
+
+// Ascending bitonic sort of 64 * NS keys held in registers, key e in slot e / 64 of lane e % 64 (pad with the
+// largest key).  Compare-exchange steps at distances below 64 go across lanes (one exchange per slot), those at
+// distances of 64 and more pair up slots of the same lane.  No memory is touched.
+template <int NS, int D>
+__device__ __forceinline__ void bitonic_slot_step(u64 (&x)[NS], u32 k) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        if ((s & D) == 0) {
+            const bool asc = ((64u * (u32)s) & k) == 0;
+            const u64 a = x[s], b = x[s | D];
+            const u64 lo = a < b ? a : b, hi = a < b ? b : a;
+            x[s] = asc ? lo : hi;
+            x[s | D] = asc ? hi : lo;
+        }
+}
+
+template <int NS>
+__device__ __forceinline__ void bitonic_registers(u64 (&x)[NS], int lane) {
+    for (u32 k = 2; k <= 64u * NS; k <<= 1) {
+        // slot distance D pairs keys 64 D apart: part of the stages k >= 128 D
+        if constexpr (NS >= 32) { if (k >= 16u * 128u) bitonic_slot_step<NS, 16>(x, k); }
+        if constexpr (NS >= 16) { if (k >= 8u * 128u) bitonic_slot_step<NS, 8>(x, k); }
+        if constexpr (NS >= 8) { if (k >= 4u * 128u) bitonic_slot_step<NS, 4>(x, k); }
+        if constexpr (NS >= 4) { if (k >= 2u * 128u) bitonic_slot_step<NS, 2>(x, k); }
+        if constexpr (NS >= 2) { if (k >= 128u) bitonic_slot_step<NS, 1>(x, k); }
+        for (u32 j = (k >> 1) < 32u ? (k >> 1) : 32u; j > 0; j >>= 1) {
+            const bool lower = ((u32)lane & j) == 0;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const u64 other = (u64)__shfl_xor((unsigned long long)x[s], (int)j, 64);
+                const bool asc = ((64u * (u32)s + (u32)lane) & k) == 0;
+                const u64 lo = x[s] < other ? x[s] : other, hi = x[s] < other ? other : x[s];
+                x[s] = (lower == asc) ? lo : hi;
+            }
+        }
+    }
 }
 
 // Sorts the n keys in `a` ascending and returns where the result lives.  Working sets whose lists
@@ -182,9 +223,13 @@ struct Wave {
     // per query
     static constexpr int QV = NQ * EPC / 4;         // float4 registers holding the query
     static constexpr bool RINGS_IN_HBM = NW > 2;    // matches the host's LDS carve-up
+    static constexpr bool BIG = NW > 2;             // large working sets: W unsorted, see admit_unsorted
+    u64 wmax;                       // BIG: key of W's farthest member, valid while nW == b
+    u64 nx_key;                     // BIG: key of the node to expand next (PAG_KEY_INVALID: W has no unvisited node)
+    bool nx_known;                  // BIG: nx_key is up to date
     float4 q[QV];
     u64 W[NW];
-    u64 RL[NW];
+    u64 RL[NW > 2 ? 1 : NW];        // unused for large working sets: their R_L is SA[0, nRL)
     u32 nW, nRL;
     u32 cntF, hdF, cntT, hdT;       // rings: valid entries (<= b) and total pushes; slot = push number & ring mask
     u32 n_hash, n_spill;
@@ -214,8 +259,10 @@ struct Wave {
         SA = (u64*)(smem + a.off_sa);
         SB = (u64*)(smem + a.off_sb);
         if constexpr (RINGS_IN_HBM) {
-            RF = a.rings + (u64)blockIdx.x * 2 * (a.ring_mask + 1);
+            RF = a.rings + (u64)blockIdx.x * 3 * (u64)(a.ring_mask + 1);
             RT = RF + (a.ring_mask + 1);
+            SA = RT + (a.ring_mask + 1);      // R_L of large working sets: b <= ring_mask + 1 keys
+            SB = nullptr;
         } else {
             RF = (u64*)(smem + a.off_rf);
             RT = (u64*)(smem + a.off_rt);
@@ -408,14 +455,22 @@ struct Wave {
         const u32 np = (u32)__popcll(mask);
         if (np == 0) {
             set_priority(0);
-            u32 zero[NW];
+            if constexpr (BIG) {
+                look_ahead();
+            } else {
+                u32 zero[NW];
 #pragma unroll
-            for (int s = 0; s < NW; ++s) zero[s] = 0;
-            request_next(zero, false, 0, 0, id_lane);
+                for (int s = 0; s < NW; ++s) zero[s] = 0;
+                request_next(zero, false, 0, 0, id_lane);
+            }
             return;
         }
         const u32 b = A.b;
         const bool pass = (mask >> lane) & 1ull;
+        if constexpr (BIG) {
+            admit_unsorted(id_lane, mask, np, pass);
+            return;
+        }
         PAG_MARK(2);
         const float dist = exact_keys(id_lane, mask);
         set_priority(0);
@@ -505,6 +560,123 @@ struct Wave {
         PAG_MARK(4);
     }
 
+    // ---- working sets above 128 nodes (NW >= 4): W is kept unsorted ----
+    // Keeping up to 1024 keys sorted by rank costs a pass over all NW slots per passer and a round trip of the
+    // whole set through LDS per hop.  What a hop needs of W is only its closest unvisited member, its farthest
+    // member and the replacement of that one; the order of the rest matters at the round's end alone, where
+    // everything is sorted anyway.
+
+    // key of the closest unvisited member of W (PAG_KEY_INVALID if there is none)
+    __device__ __forceinline__ u64 min_unvisited() const {
+        u64 m = PAG_KEY_INVALID;
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
+            const u32 idx = s * 64 + lane;
+            const u64 k = (idx < nW && !(W[s] & 1ull)) ? W[s] : PAG_KEY_INVALID;
+            m = k < m ? k : m;
+        }
+        return wave_extreme<false>(m);
+    }
+
+    __device__ __forceinline__ u64 max_member() const {
+        u64 m = 0;
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
+            const u32 idx = s * 64 + lane;
+            const u64 k = idx < nW ? W[s] : 0ull;
+            m = k > m ? k : m;
+        }
+        return wave_extreme<true>(m);
+    }
+
+    // finds the node that will be expanded next and requests its adjacency record
+    __device__ __forceinline__ void look_ahead() {
+        nx_key = min_unvisited();
+        nx_known = true;
+        nx_id = PAG_EMPTY;
+        if (nx_key != PAG_KEY_INVALID) {
+            nx_id = (u32)(nx_key & 0xFFFFFFFFull) >> 1;
+            load_record(nx_id, pf_id, pf_a, pf_c, pf_cw);
+        }
+    }
+
+    // Admission into an unsorted W.  The hop's passers are taken in ascending (dist, id) order, exactly as Alg. 2
+    // admits them one after the other: while W has room a passer is appended; then a passer closer than W's
+    // farthest member takes that member's place and the member goes to R_T; the first passer that is not closer
+    // ends it -- the farthest member can only have come closer since, and the remaining passers are no smaller --,
+    // and that passer and all after it go to R_F.
+    __device__ __forceinline__ void admit_unsorted(u32 id_lane, u64 mask, u32 np, bool pass) {
+        const u32 b = A.b;
+        PAG_MARK(2);
+        const float dist = exact_keys(id_lane, mask);
+        set_priority(0);
+        PAG_MARK(3);
+        s_exact += np;
+        if (A.blog != 0) {
+            if (pass) {
+                H[hash_slot(id_lane, A.hlog)] = id_lane;
+                atomicOr(&bitmap[id_lane >> 5], 1u << (id_lane & 31));
+                bloom_set(BL, A.blog, id_lane);
+            }
+            n_spill += np; s_spill += np;
+        } else {
+            const bool spill = (n_hash + np) > (1u << (A.hlog - 1));
+            if (pass) {
+                if (!spill) hash_insert(H, A.hlog, id_lane);
+                else atomicOr(&bitmap[id_lane >> 5], 1u << (id_lane & 31));
+            }
+            if (spill) { n_spill += np; s_spill += np; } else n_hash += np;
+        }
+        const u64 pk = pass ? (((u64)__float_as_uint(dist) << 32) | ((u64)id_lane << 1)) : PAG_KEY_INVALID;
+        // rank of my passer among the hop's passers (keys are distinct)
+        u32 cP = 0;
+        for (u64 m = mask; m;) {
+            const int p = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            cP += (rdlane64(pk, p) < pk) ? 1u : 0u;
+        }
+        u32 n_ej = 0, j = 0;
+        for (; j < np; ++j) {
+            const int src = __ffsll((long long)__ballot(pass && cP == j)) - 1;
+            const u64 k = rdlane64(pk, src);
+            if (nW < b) {
+                const u32 slot = nW >> 6, ln = nW & 63u;
+#pragma unroll
+                for (int s = 0; s < NW; ++s)
+                    if ((u32)s == slot && (u32)lane == ln) W[s] = k;
+                nW++;
+                if (nW == b) wmax = max_member();
+            } else if (k < wmax) {
+                // the farthest member leaves for R_T (pushes of one hop: farthest first), the passer takes its slot
+                if (lane == 0) RT[(hdT + n_ej) & A.ring_mask] = wmax;
+                n_ej++;
+#pragma unroll
+                for (int s = 0; s < NW; ++s)
+                    if ((W[s] | 1ull) == (wmax | 1ull)) W[s] = k;
+                wmax = max_member();
+            } else {
+                break;
+            }
+        }
+        const u32 n_f = np - j;                                     // false positives -> R_F, smallest first
+        if (pass && cP >= j) {
+            const u32 oi = cP - j;
+            if (oi + b >= n_f) RF[(hdF + oi) & A.ring_mask] = pk;   // older ones would be overwritten anyway
+        }
+        if (n_ej) {
+            if (cntT + n_ej > b) s_rt += cntT + n_ej - b;
+            cntT = cntT + n_ej < b ? cntT + n_ej : b;
+            hdT += n_ej;
+        }
+        if (n_f) {
+            if (cntF + n_f > b) s_rf += cntF + n_f - b;
+            cntF = cntF + n_f < b ? cntF + n_f : b;
+            hdF += n_f;
+        }
+        look_ahead();
+        PAG_MARK(4);
+    }
+
     __device__ __forceinline__ void run_query(u32 qi) {
         const u32 d = A.d, b = A.b, deg = A.deg;
         // ---- load query, table, reset state ----
@@ -530,12 +702,15 @@ struct Wave {
                 for (u32 i = lane; i < (1u << A.blog) / 128; i += 64) ((uint4*)BL)[i] = z4;
             }
 #pragma unroll
-            for (int s = 0; s < NW; ++s) { W[s] = PAG_KEY_INVALID; RL[s] = PAG_KEY_INVALID; }
+            for (int s = 0; s < NW; ++s) W[s] = PAG_KEY_INVALID;
+#pragma unroll
+            for (int s = 0; s < (BIG ? 1 : NW); ++s) RL[s] = PAG_KEY_INVALID;
             nW = nRL = 0;
             cntF = hdF = cntT = hdT = 0;
             n_hash = n_spill = 0;
             Hk = PAG_KEY_INVALID;
             nx_id = PAG_EMPTY;
+            wmax = 0; nx_key = PAG_KEY_INVALID; nx_known = false;
             __syncthreads();
         }
         s_queries++;
@@ -559,22 +734,34 @@ struct Wave {
             s_rounds++;
             for (;;) {
                 // closest unvisited member of W
-                int us = -1, ul = 0;
-#pragma unroll
-                for (int s = 0; s < NW; ++s) {
-                    const u32 idx = s * 64 + lane;
-                    const u64 m = __ballot(idx < nW && !(W[s] & 1ull));
-                    if (us < 0 && m) { us = s; ul = __ffsll((long long)m) - 1; }
-                }
-                if (us < 0) break;
-                PAG_MARK(5);
                 u64 ukey = 0;
+                if constexpr (BIG) {
+                    if (!nx_known) nx_key = min_unvisited();
+                    nx_known = false;
+                    if (nx_key == PAG_KEY_INVALID) break;
+                    PAG_MARK(5);
+                    ukey = nx_key;
 #pragma unroll
-                for (int s = 0; s < NW; ++s)
-                    if (s == us) {
-                        ukey = rdlane64(W[s], ul);
-                        if (lane == ul) W[s] |= 1ull;
+                    for (int s = 0; s < NW; ++s)
+                        if (W[s] == ukey) W[s] |= 1ull;
+                    if (nW == b && (wmax | 1ull) == (ukey | 1ull)) wmax |= 1ull;
+                } else {
+                    int us = -1, ul = 0;
+#pragma unroll
+                    for (int s = 0; s < NW; ++s) {
+                        const u32 idx = s * 64 + lane;
+                        const u64 m = __ballot(idx < nW && !(W[s] & 1ull));
+                        if (us < 0 && m) { us = s; ul = __ffsll((long long)m) - 1; }
                     }
+                    if (us < 0) break;
+                    PAG_MARK(5);
+#pragma unroll
+                    for (int s = 0; s < NW; ++s)
+                        if (s == us) {
+                            ukey = rdlane64(W[s], ul);
+                            if (lane == ul) W[s] |= 1ull;
+                        }
+                }
                 s_hops++;
                 set_priority(2);   // screening leads to the next loads: ahead of other waves' bookkeeping
                 const u32 u = (u32)(ukey & 0xFFFFFFFFull) >> 1;
@@ -582,10 +769,14 @@ struct Wave {
                 // threshold ||z_max - q||^2, read once per hop (Eq. 4); +inf while W is not full
                 float Dmax = __builtin_inff();
                 if (nW == b) {
-                    const u32 wr = b - 1;
+                    if constexpr (BIG) {
+                        Dmax = __uint_as_float((u32)(wmax >> 32));
+                    } else {
+                        const u32 wr = b - 1;
 #pragma unroll
-                    for (int s = 0; s < NW; ++s)
-                        if ((int)(wr >> 6) == s) Dmax = __uint_as_float(rdlane((u32)(W[s] >> 32), wr & 63));
+                        for (int s = 0; s < NW; ++s)
+                            if ((int)(wr >> 6) == s) Dmax = __uint_as_float(rdlane((u32)(W[s] >> 32), wr & 63));
+                    }
                 }
                 PAG_MARK(0);
                 // adjacency record of u: normally already on its way (see request_next)
@@ -668,6 +859,23 @@ struct Wave {
                     if (idx < nW && n_cand + idx < A.cand_cap) A.cand[(u64)qi * A.cand_cap + n_cand + idx] = W[s];
                 }
                 n_cand = n_cand + nW < A.cand_cap ? n_cand + nW : A.cand_cap;
+            } else if constexpr (BIG) {
+                // R_L <- best K of R_L + W: R_L (sorted, SA[0, nRL) in HBM) and W are sorted together in registers
+                u64 x[2 * NW];
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    const u32 idx = s * 64 + lane;
+                    x[s] = idx < nW ? W[s] : PAG_KEY_INVALID;
+                    x[NW + s] = idx < nRL ? SA[idx] : PAG_KEY_INVALID;
+                }
+                bitonic_registers<2 * NW>(x, lane);
+                const u32 n = nRL + nW;
+                nRL = n < A.K ? n : A.K;
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {                  // K <= b <= 64 NW
+                    const u32 idx = s * 64 + lane;
+                    if (idx < nRL) SA[idx] = x[s];
+                }
             } else {
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
@@ -686,9 +894,43 @@ struct Wave {
                 }
                 lds_sync();
             }
-            {
-                // rings in HBM: this wave's own pushes (by other lanes) must have landed before they are read
-                if constexpr (RINGS_IN_HBM) __threadfence();
+            if constexpr (BIG) {
+                // this wave's own stores (ring pushes, R_L) must have landed before other lanes read them
+                __threadfence();
+                const u32 n = cntF + cntT;                       // <= 2b <= 128 NW
+                u64 x[2 * NW];
+#pragma unroll
+                for (int s = 0; s < 2 * NW; ++s) {
+                    const u32 i = s * 64 + lane;
+                    u64 k = PAG_KEY_INVALID;
+                    if (i < cntF) k = RF[(hdF - cntF + i) & A.ring_mask];
+                    else if (i < n) k = RT[(hdT - cntT + (i - cntF)) & A.ring_mask];
+                    x[s] = k;
+                }
+                bitonic_registers<2 * NW>(x, lane);
+                nW = n < b ? n : b;
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    const u32 idx = s * 64 + lane;
+                    W[s] = idx < nW ? x[s] : PAG_KEY_INVALID;
+                }
+                wmax = 0ull;
+                if (nW == b) {                                   // key b - 1 of the sorted list
+                    const u32 wr = b - 1;
+#pragma unroll
+                    for (int s = 0; s < NW; ++s)
+                        if ((int)(wr >> 6) == s) wmax = rdlane64(x[s], wr & 63);
+                }
+                nx_known = false;
+                const u32 rest = n - nW;                         // <= b; written worst first
+#pragma unroll
+                for (int s = 0; s < 2 * NW; ++s) {
+                    const u32 e = s * 64 + lane;
+                    if (e >= nW && e < n) RT[n - 1 - e] = x[s];
+                }
+                cntT = rest; hdT = rest;
+                cntF = 0; hdF = 0;
+            } else {
                 for (u32 i = lane; i < cntF; i += 64) SA[i] = RF[(hdF - cntF + i) & A.ring_mask];
                 for (u32 i = lane; i < cntT; i += 64) SA[cntF + i] = RT[(hdT - cntT + i) & A.ring_mask];
                 lds_sync();
@@ -720,8 +962,11 @@ struct Wave {
                     long long oid = -1;
                     float od = __builtin_inff();
                     if (idx < nRL) {
-                        oid = (long long)((u32)(RL[s] & 0xFFFFFFFFull) >> 1);
-                        od = A.out_scale * __uint_as_float((u32)(RL[s] >> 32));
+                        u64 key;
+                        if constexpr (BIG) key = SA[idx];
+                        else key = RL[s];
+                        oid = (long long)((u32)(key & 0xFFFFFFFFull) >> 1);
+                        od = A.out_scale * __uint_as_float((u32)(key >> 32));
                     }
                     A.out_ids[(u64)qi * A.K + idx] = oid;
                     A.out_dists[(u64)qi * A.K + idx] = od;
@@ -760,8 +1005,9 @@ struct Wave {
 // passes nq.
 template <int NQ, int NW, int VM, int CW>
 // Short rows leave room for four waves per SIMD (128 VGPRs, a few dwords of spill); longer rows
-// keep their registers for loads in flight.
-__attribute__((amdgpu_waves_per_eu(VM == 2 && NQ <= 3 && NW <= 2 ? 5 : (NQ <= 3 && NW <= 2 ? 4 : 1), 8)))
+// keep their registers for loads in flight.  Working sets above 128 nodes hold W in 4 NW registers per lane:
+// three waves per SIMD up to 512 nodes, two for 1024 (measured: a third wave there spills W and costs 50 %).
+__attribute__((amdgpu_waves_per_eu(VM == 2 && NQ <= 3 && NW <= 2 ? 5 : (NQ <= 3 && NW <= 2 ? 4 : (NQ <= 4 && NW > 2 ? (NW >= 16 ? 2 : 3) : 1)), 8)))
 __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
     extern __shared__ __align__(64) unsigned char smem[];   // the table sits first: see table_sum
     const int lane = threadIdx.x;

@@ -71,4 +71,31 @@ __device__ __forceinline__ double fold_total(double tot, int g) {
                             __builtin_amdgcn_readlane(__double2loint(tot), src));
 }
 
+// Wave-wide minimum / maximum of one 64-bit key per lane, result in every lane: four DPP steps
+// within the rows of 16 lanes, two exchanges across the rows.
+template <int CTRL>
+__device__ __forceinline__ u64 dpp_move_u64(u64 x) {
+    int lo = (int)(u32)x, hi = (int)(u32)(x >> 32);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, false);
+    return ((u64)(u32)hi << 32) | (u32)lo;
+}
+
+template <bool MAX>
+__device__ __forceinline__ u64 pick(u64 a, u64 b) {
+    if constexpr (MAX) return a > b ? a : b;
+    else return a < b ? a : b;
+}
+
+template <bool MAX>
+__device__ __forceinline__ u64 wave_extreme(u64 x) {
+    x = pick<MAX>(x, dpp_move_u64<0xB1>(x));     // quad_perm [1,0,3,2]
+    x = pick<MAX>(x, dpp_move_u64<0x4E>(x));     // quad_perm [2,3,0,1]
+    x = pick<MAX>(x, dpp_move_u64<0x141>(x));    // row_half_mirror
+    x = pick<MAX>(x, dpp_move_u64<0x140>(x));    // row_mirror
+    x = pick<MAX>(x, (u64)__shfl_xor((unsigned long long)x, 16, 64));
+    x = pick<MAX>(x, (u64)__shfl_xor((unsigned long long)x, 32, 64));
+    return x;
+}
+
 }  // namespace pagk
