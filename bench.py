@@ -33,7 +33,7 @@ T_START = time.time()
 
 # what the secondary workloads took on an MI355X machine (generation on the host, build, ground truth, sweep, timing),
 # with some margin: a workload only starts if it fits what is left of the budget
-SECONDARY_SECONDS = {3: 75.0, 5: 150.0, 4: 230.0}
+SECONDARY_SECONDS = {3: 45.0, 5: 130.0, 4: 130.0}
 
 
 def log(*a):
