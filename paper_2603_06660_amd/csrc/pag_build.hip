@@ -530,8 +530,9 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
             const u32 lds = L.d * 4 + 2 * n_init * 8;
             hipLaunchKernelGGL(k_init_clique, dim3(n_init), dim3(64), lds, s, pag_vecs_of(ix), ix->rec, L, ws.order, n_init);
             PAG_HIP(hipGetLastError());
-            if ((rc = pag_launch_edge_info_of(s, ix, ws.order, n_init))) return rc;
         }
+        // also for a lone first node: its record leaves this pass with clean free slots
+        if ((rc = pag_launch_edge_info_of(s, ix, ws.order, n_init))) return rc;
         done = n_init;
     }
     ix->n_entry = (u32)std::min<u64>(entry_before + done, 1024);

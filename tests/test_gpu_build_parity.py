@@ -239,3 +239,47 @@ def test_crowded_insert(orc):
     ex = gix.export()
     assert np.array_equal(ex["vectors"], oix.vec)
     _assert_same_index(ex, oix, "crowded insert")
+
+
+@pytest.mark.parametrize("n,d,P,deg,efC,subbatch", [
+    (1, 32, 4, 8, 20, 0),          # a single node
+    (2, 32, 4, 8, 20, 1),
+    (7, 32, 4, 8, 20, 0),          # fewer nodes than the degree and than the initial set
+    (21, 32, 4, 8, 20, 1),         # one node more than the initial set
+    (150, 64, 8, 64, 120, 0),      # the largest degree; the initial set (100 nodes) is most of the index
+    (260, 3072, 64, 16, 60, 0),    # the longest rows and most subspaces this build takes
+    (300, 72, 9, 11, 40, 0),       # ragged: 72 = 9 x 8, odd degree
+])
+def test_small_and_extreme_shapes(orc, n, d, P, deg, efC, subbatch):
+    """Construction at the edges of what the library accepts, against the oracle (sequential or in the
+    default batches, PES on)."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_KEEP_ORDER
+    rng = np.random.default_rng(1000 * n + d)
+    base = rng.standard_normal((n, d)).astype(np.float32)
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric="l2", max_degree=deg, num_subspaces=P,
+                         ef_construction=efC, insert_subbatch=subbatch, seed=61, flags=FLAG_KEEP_ORDER)
+    ex = gix.export()
+    kw = dict(pes_every=1) if subbatch else dict(max_batch=min(n, 1024))
+    oix = _oracle_on(orc, ex, np.arange(n), base, deg=deg, P=P, efC=efC, pes=True, **kw)
+    _assert_same_index(ex, oix, "shape n=%d d=%d" % (n, d))
+    assert ex["entry"].tolist() == list(range(n))
+
+
+def test_duplicated_vectors(orc):
+    """Every vector of the second half repeats one of the first: zero-length edges, exact ties between
+    distances everywhere (ordered by id on both sides, the ids being the same: rows are linked in the order
+    given), RobustPrune's `<=` deciding between equals.  Sequential and batched."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_KEEP_ORDER
+    rng = np.random.default_rng(99)
+    half = rng.standard_normal((400, 64)).astype(np.float32)
+    base = np.concatenate([half, half[rng.permutation(400)]])
+    for subbatch in (1, 0):
+        gix = PagIndex.build(torch.from_numpy(base).cuda(), metric="l2", max_degree=16, num_subspaces=8,
+                             ef_construction=64, insert_subbatch=subbatch, seed=67, flags=FLAG_KEEP_ORDER)
+        ex = gix.export()
+        kw = dict(pes_every=1) if subbatch else dict(max_batch=800)
+        oix = _oracle_on(orc, ex, np.arange(800), base, deg=16, P=8, efC=64, pes=True, **kw)
+        _assert_same_index(ex, oix, "duplicates")
+        assert ((ex["e2"] == 0) & (ex["adj"] != orc.EMPTY)).sum() > 100
