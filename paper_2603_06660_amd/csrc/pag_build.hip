@@ -65,33 +65,37 @@ __device__ __forceinline__ void dist_lds4(const pag_vecs& V, u32 d, const float*
     for (int g = 0; g < 4; ++g) out[g] = (float)pagk::fold_total<4>(tot, g);
 }
 
-// the same for two staged vectors at once: the four rows are fetched once and used twice
-__device__ __forceinline__ void dist_lds4x2(const pag_vecs& V, u32 d, const float* s0, const float* s1, const u32 (&id)[4],
-                                            float (&out0)[4], float (&out1)[4]) {
-    const float4 *q0 = (const float4*)s0, *q1 = (const float4*)s1;
-    double acc0[4] = {0.0, 0.0, 0.0, 0.0}, acc1[4] = {0.0, 0.0, 0.0, 0.0};
+// the same for C staged vectors at once: the four rows are fetched once and used C times
+template <int C>
+__device__ __forceinline__ void dist_lds4xC(const pag_vecs& V, u32 d, const float* s0, const u32 (&id)[4], float (&out)[C][4]) {
+    double acc[C][4];
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) acc[i][g] = 0.0;
     for (u32 c = threadIdx.x; c < d / 4; c += 64) {
-        const float4 a0 = q0[c], a1 = q1[c];
         float4 b[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) b[g] = pag_vload4(V, id[g], c);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            float dx = a0.x - b[g].x, dy = a0.y - b[g].y, dz = a0.z - b[g].z, dw = a0.w - b[g].w;
-            acc0[g] = __builtin_fma((double)dx, (double)dx, acc0[g]);
-            acc0[g] = __builtin_fma((double)dy, (double)dy, acc0[g]);
-            acc0[g] = __builtin_fma((double)dz, (double)dz, acc0[g]);
-            acc0[g] = __builtin_fma((double)dw, (double)dw, acc0[g]);
-            dx = a1.x - b[g].x; dy = a1.y - b[g].y; dz = a1.z - b[g].z; dw = a1.w - b[g].w;
-            acc1[g] = __builtin_fma((double)dx, (double)dx, acc1[g]);
-            acc1[g] = __builtin_fma((double)dy, (double)dy, acc1[g]);
-            acc1[g] = __builtin_fma((double)dz, (double)dz, acc1[g]);
-            acc1[g] = __builtin_fma((double)dw, (double)dw, acc1[g]);
+        for (int i = 0; i < C; ++i) {
+            const float4 a = ((const float4*)(s0 + (size_t)i * d))[c];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float dx = a.x - b[g].x, dy = a.y - b[g].y, dz = a.z - b[g].z, dw = a.w - b[g].w;
+                acc[i][g] = __builtin_fma((double)dx, (double)dx, acc[i][g]);
+                acc[i][g] = __builtin_fma((double)dy, (double)dy, acc[i][g]);
+                acc[i][g] = __builtin_fma((double)dz, (double)dz, acc[i][g]);
+                acc[i][g] = __builtin_fma((double)dw, (double)dw, acc[i][g]);
+            }
         }
     }
-    const double t0 = pagk::fold_sum<4>(acc0), t1 = pagk::fold_sum<4>(acc1);
 #pragma unroll
-    for (int g = 0; g < 4; ++g) { out0[g] = (float)pagk::fold_total<4>(t0, g); out1[g] = (float)pagk::fold_total<4>(t1, g); }
+    for (int i = 0; i < C; ++i) {
+        const double t = pagk::fold_sum<4>(acc[i]);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) out[i][g] = (float)pagk::fold_total<4>(t, g);
+    }
 }
 
 // squared distance between two vectors staged in LDS, all lanes get the result
@@ -165,18 +169,21 @@ __global__ void k_cand_segments(const u32* __restrict__ cand_cnt, u32 m, u32 can
 // sorted ascending by a segmented radix sort over bits 1..63.  Cut to efC, then scanned: a candidate is kept unless an
 // already kept s has ||s - c|| <= ||v - c||.  Writes N_out(v) into v's record and one reverse
 // pair per kept neighbour: key = target << 32 | dist bits, value = v.
+// The kernel is bound by the rows it fetches (a node's kept rows do not stay in any cache while thousands of
+// nodes are pruned at once): candidates are therefore taken C at a time, staged in LDS, so that one pass over
+// the kept rows serves all C.
+template <int C>
 __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restrict__ recs,
                                                   pag_layout L, const u32* __restrict__ nodes, u32 m,
                                                   const u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
                                                   const u64* __restrict__ pes, float* __restrict__ e2,
                                                   u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
     extern __shared__ __align__(16) unsigned char smem[];
-    float* sv = (float*)smem;                  // [2][d] candidate vectors
-    u32* kept = (u32*)(sv + 2 * L.d);          // [deg]
+    float* sv = (float*)smem;                  // [C][d] candidate vectors
+    u32* kept = (u32*)(sv + (size_t)C * L.d);  // [deg]
     const u32 vi = blockIdx.x;
     if (vi >= m) return;
-    // the sorted list lives in HBM: it is read once, front to back, and keeping it out of LDS lets
-    // many waves hide each other's row-fetch latency
+    // the sorted list lives in HBM: it is read once, front to back
     const u64* sorted = cand_sorted + (u64)vi * cand_cap;   // ascending by (dist, id); bit 0 is the visited flag
     const int lane = threadIdx.x;
     const u32 v = nodes[vi];
@@ -186,38 +193,53 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
     u32 nk = 0;
     u32 my_id = PAG_EMPTY;       // lane s holds kept[s]
     u32 my_key = 0;
-    // Candidates are taken two at a time: both are tested against the neighbours kept so far with one
-    // pass over those rows, and the second additionally against the first if that one has just been kept,
-    // which is what testing them one after the other amounts to.
-    float* sv1 = sv + L.d;                     // the second candidate
-    for (u32 ci = 0; ci < nc && nk < L.deg; ci += 2) {
-        const bool two = ci + 1 < nc;
-        const u64 k1 = sorted[ci], k2 = two ? sorted[ci + 1] : k1;
-        const u32 c1 = (u32)(k1 & 0xFFFFFFFFull) >> 1, c2 = (u32)(k2 & 0xFFFFFFFFull) >> 1;
-        const float dv1 = __uint_as_float((u32)(k1 >> 32)), dv2 = __uint_as_float((u32)(k2 >> 32));
-        stage(vec, L.d, c1, sv, lane);
-        stage(vec, L.d, c2, sv1, lane);
+    // C candidates at a time: all are tested against the neighbours kept so far with one pass over those rows,
+    // and each additionally against the earlier ones of its group that have just been kept, which is what
+    // testing them one after the other amounts to.
+    for (u32 ci = 0; ci < nc && nk < L.deg; ci += C) {
+        u64 key[C];
+        u32 cid[C];
+        float dv[C];
+        bool occ[C];
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const bool there = ci + i < nc;
+            key[i] = sorted[there ? ci + i : nc - 1];
+            cid[i] = (u32)(key[i] & 0xFFFFFFFFull) >> 1;
+            dv[i] = __uint_as_float((u32)(key[i] >> 32));
+            // a node that is searched for a second time finds itself: never its own neighbour
+            occ[i] = !there || cid[i] == v;
+            stage(vec, L.d, cid[i], sv + (size_t)i * L.d, lane);
+        }
         __syncthreads();
-        // a node that is searched for a second time finds itself: never its own neighbour
-        bool occ1 = c1 == v, occ2 = !two || c2 == v;
-        for (u32 s0 = 0; s0 < nk && !(occ1 && occ2); s0 += 4) {
+        for (u32 s0 = 0; s0 < nk; s0 += 4) {
+            bool all = true;
+#pragma unroll
+            for (int i = 0; i < C; ++i) all = all && occ[i];
+            if (all) break;
             u32 sid[4];
-            float d1[4], d2[4];
+            float dd[C][4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) sid[g] = kept[s0 + g < nk ? s0 + g : nk - 1];   // a repeated last entry changes nothing
-            dist_lds4x2(vec, L.d, sv, sv1, sid, d1, d2);
+            dist_lds4xC<C>(vec, L.d, sv, sid, dd);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) { occ1 = occ1 || d1[g] <= dv1; occ2 = occ2 || d2[g] <= dv2; }
+            for (int i = 0; i < C; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) occ[i] = occ[i] || dd[i][g] <= dv[i];
         }
-        if (!occ1) {
-            if ((u32)lane == nk) { my_id = c1; my_key = (u32)(k1 >> 32); kept[nk] = c1; }
-            nk++;
-        }
-        if (two && nk < L.deg) {
-            if (!occ1 && !occ2) occ2 = dist_lds_lds(L.d, sv, sv1) <= dv2;
-            if (!occ2) {
-                if ((u32)lane == nk) { my_id = c2; my_key = (u32)(k2 >> 32); kept[nk] = c2; }
-                nk++;
+        bool kept_here[C];
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            kept_here[i] = false;
+            if (nk < L.deg) {
+#pragma unroll
+                for (int j = 0; j < i; ++j)
+                    if (kept_here[j] && !occ[i]) occ[i] = dist_lds_lds(L.d, sv + (size_t)j * L.d, sv + (size_t)i * L.d) <= dv[i];
+                if (!occ[i]) {
+                    if ((u32)lane == nk) { my_id = cid[i]; my_key = (u32)(key[i] >> 32); kept[nk] = cid[i]; }
+                    nk++;
+                    kept_here[i] = true;
+                }
             }
         }
         __syncthreads();
@@ -570,9 +592,17 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         if ((rc = search_candidates(ix, ws, ix->ws_qrot, m, b, cand_cap, n_end))) return rc;
         //    RobustPrune -> N_out(v), reverse pairs
         {
-            const u32 plds = 2 * L.d * 4 + L.deg * 4;
-            hipLaunchKernelGGL(k_prune_new, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, nodes, (u32)m,
-                               ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ix->e2, ws.rk_in, ws.rv_in);
+            // four candidates per pass over the kept rows where their staging fits 16 KB of LDS per wave (about a tenth
+            // faster there), else two: with longer rows the lost occupancy cancels the saved reads
+            if (4u * L.d * 4 <= 16384u) {
+                const u32 plds = 4 * L.d * 4 + L.deg * 4;
+                hipLaunchKernelGGL(k_prune_new<4>, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, nodes, (u32)m,
+                                   ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ix->e2, ws.rk_in, ws.rv_in);
+            } else {
+                const u32 plds = 2 * L.d * 4 + L.deg * 4;
+                hipLaunchKernelGGL(k_prune_new<2>, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, nodes, (u32)m,
+                                   ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ix->e2, ws.rk_in, ws.rv_in);
+            }
             PAG_HIP(hipGetLastError());
         }
         PAG_HIP(hipEventRecord(ws.ev[2], s));
