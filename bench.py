@@ -544,15 +544,19 @@ def main():
                 continue
             t0 = time.time()
             w2 = wl.workload(cfg)
-            if cfg == 5:
-                others["cfg5"] = online_insertion(args, w2, wl, torch, np, PagIndex)
-            else:
-                r2 = search_workload(args, w2, wl, torch, np, PagIndex, steps=5, warmup=2,
-                                     extra_K=(10, 50) if cfg == 4 else ())
-                others["cfg%d" % cfg] = compact(r2)
-                r2["ix"].close()
-                del r2
-                torch.cuda.empty_cache()
+            try:
+                if cfg == 5:
+                    others["cfg5"] = online_insertion(args, w2, wl, torch, np, PagIndex)
+                else:
+                    r2 = search_workload(args, w2, wl, torch, np, PagIndex, steps=5, warmup=2,
+                                         extra_K=(10, 50) if cfg == 4 else ())
+                    others["cfg%d" % cfg] = compact(r2)
+                    r2["ix"].close()
+                    del r2
+            except Exception as ex:          # a secondary workload must not cost the run its headline line
+                log("cfg%d failed: %r" % (cfg, ex))
+                others["cfg%d" % cfg] = {"error": repr(ex)}
+            torch.cuda.empty_cache()
             others["cfg%d" % cfg]["wall_seconds"] = round(time.time() - t0, 1)
         others["left_out"] = left_out
         config["other_workloads"] = others
