@@ -116,7 +116,8 @@ def search_workload(args, w, wl, torch, np, PagIndex, *, steps, warmup, efs_fixe
     gt_big, _ = wl.brute_force_torch(base_d, q_d, max(Ks), w.metric)
     for k in Ks:
         gts[k] = gt_big[:, :k]
-    log("ground truth: %.1f s" % (time.time() - t0))
+    gt_s = time.time() - t0
+    log("ground truth: %.1f s" % gt_s)
     del base_d
     torch.cuda.empty_cache()
 
@@ -227,7 +228,7 @@ def search_workload(args, w, wl, torch, np, PagIndex, *, steps, warmup, efs_fixe
                 "frac_of_measured_hop_traffic": round(t["achieved"] / hop_gbs, 4)}
     res = {"w": w, "K": K, "ix": ix, "q": q, "q_d": q_d, "ids": t["ids"], "efS": efS, "recall": recall, "reached": reached,
            "interp": interp, "curve": curve, "qps": t["qps"], "ms_per_step": t["ms_per_step"], "counters": c,
-           "skipped": skipped, "roofline": roofline, "build": build, "build_s": build_s, "vec_bytes": vec_bytes,
+           "skipped": skipped, "roofline": roofline, "build": build, "build_s": build_s, "vec_bytes": vec_bytes, "gt_s": gt_s,
            "timed": timed, "gts": gts, "hop_gbs": hop_gbs}
     # further retrieval sizes on the same index (cfg 4: K = 10 and K = 50)
     res["extra_K"] = {}
@@ -526,7 +527,9 @@ def main():
               "skipped_fraction_of_unseen_neighbours": round(res["skipped"], 4),
               "hops_per_query": round(c["hops"] / max(1, c["queries"]), 1),
               "exact_per_query": round(c["exact"] / max(1, c["queries"]), 1),
-              "build_seconds": round(res["build_s"], 2), "build": res["build"], "sweep": res["curve"], "tuned": tuned}
+              "build_seconds": round(res["build_s"], 2), "build": res["build"], "sweep": res["curve"], "tuned": tuned,
+              # for scale: exhaustive search of the same batch (torch matmul + top-k on the GPU, re-ranked in fp64), the ground truth
+              "brute_force_queries_per_s": round(w.nq / res["gt_s"], 1)}
     if res["extra_K"]:
         config["other_retrieval_sizes"] = res["extra_K"]
     head = {"qps": res["qps"], "ms_per_step": res["ms_per_step"], "roofline": res["roofline"]}
