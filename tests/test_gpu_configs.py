@@ -209,6 +209,16 @@ def test_full_size_benchmark_workload(orc):
     # sampled outputs checked one by one: the reported key is the true 1 - <q, x>
     ip = np.einsum("qkd,qd->qk", base[gi[sample]].astype(np.float64), q[sample].astype(np.float64))
     assert np.allclose(gd[sample], 1.0 - ip, atol=5e-6)
+    # the search of an insertion at this size (efC = 200: two rounds of b = 100 over a million nodes): R_L and the
+    # PES buffer H(v) of 40 vectors that are not in the index, against the oracle on the exported arrays
+    fresh = q[1::250][:40].copy()
+    ci, ck, cn, hi, hk, hn = gix.insertion_candidates(torch.from_numpy(fresh).cuda(), 200)
+    fr, _ = oix.prepare(fresh)
+    for i in range(len(fresh)):
+        oi_, ok_, ohi, ohk, _ = oix.index_search(fr[i], 200)
+        assert cn[i] == len(oi_) and ci[i, :cn[i]].tolist() == oi_.tolist(), i
+        assert np.all(np.abs(ck[i, :cn[i]] - ok_) <= 1e-5 * ok_)
+        assert hn[i] == len(ohi) and hi[i, :hn[i]].tolist() == ohi.tolist(), i
 
 
 @pytest.mark.parametrize("cfg,efS", [(3, (128, 1024)), (4, (64, 640)), (5, (64, 1536))])
