@@ -134,6 +134,8 @@ def test_one_node_after_another_in_shuffled_order(orc):
     (1, 3000, 128, 16, 32, "l2", 100, 0),        # the library's own schedule: batches of up to half the graph, at most 1024
     (1, 2500, 128, 16, 32, "l2", 64, 160),
     (3, 1500, 256, 32, 48, "ip", 220, 0),
+    (1, 30000, 128, 16, 32, "l2", 100, 0),       # 35 batches, the last ones of 1024 nodes
+    (2, 12000, 256, 32, 32, "ip", 300, 0),       # three rounds per insertion, long-search seen set
 ])
 def test_default_batches(orc, cfg, n, d, P, deg, metric, efC, subbatch):
     """The batch-synchronous construction, batch schedule and all, against the oracle's."""
