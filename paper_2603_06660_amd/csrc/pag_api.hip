@@ -88,8 +88,17 @@ void orthonormalise(std::vector<double>& g, uint32_t dim, unsigned threads) {
     }
 }
 
-void make_transform(uint32_t d, uint64_t seed, std::vector<float>& rot) {
+void make_transform(uint32_t d, uint64_t seed, bool permutation, std::vector<float>& rot) {
     Rng rng(seed, 1);
+    if (permutation) {
+        // a signed permutation: row j has one entry +-1, in a column drawn by a Fisher-Yates shuffle
+        std::vector<uint32_t> col(d);
+        for (uint32_t j = 0; j < d; ++j) col[j] = j;
+        for (uint32_t j = d - 1; j > 0; --j) std::swap(col[j], col[rng.next() % (j + 1)]);
+        rot.assign((size_t)d * d, 0.f);
+        for (uint32_t j = 0; j < d; ++j) rot[(size_t)j * d + col[j]] = (rng.next() & 1) ? 1.f : -1.f;
+        return;
+    }
     std::vector<double> g((size_t)d * d);
     for (auto& x : g) x = rng.normal();
     unsigned threads = std::max(1u, std::min(8u, std::thread::hardware_concurrency()));
@@ -321,7 +330,7 @@ extern "C" int pag_build(const float* D, uint64_t n, uint32_t d, const pag_param
         const auto t0 = std::chrono::steady_clock::now();
         if ((rc = alloc_index(ix))) return rc;
         std::vector<float> rot, cb;
-        make_transform(d, params->seed, rot);
+        make_transform(d, params->seed, (params->flags & PAG_FLAG_PERMUTATION_TRANSFORM) != 0, rot);
         make_codebooks(d, L.P, params->seed, cb);
         hipError_t e = hipMemcpyAsync(ix->rot, rot.data(), rot.size() * 4, hipMemcpyHostToDevice, ix->stream);
         if (e == hipSuccess) e = hipMemcpyAsync(ix->cb, cb.data(), cb.size() * 4, hipMemcpyHostToDevice, ix->stream);

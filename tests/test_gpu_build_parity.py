@@ -285,3 +285,26 @@ def test_duplicated_vectors(orc):
         oix = _oracle_on(orc, ex, np.arange(800), base, deg=16, P=8, efC=64, pes=True, **kw)
         _assert_same_index(ex, oix, "duplicates")
         assert ((ex["e2"] == 0) & (ex["adj"] != orc.EMPTY)).sum() > 100
+
+
+@pytest.mark.parametrize("subbatch,metric", [(1, "l2"), (0, "l2"), (0, "cos")])
+def test_build_from_raw_vectors(orc, subbatch, metric):
+    """pag_build with nothing computed by the library reaching the oracle: the transform is a signed permutation
+    (PAG_FLAG_PERMUTATION_TRANSFORM), so the oracle, given the raw vectors and the library's random draws (Q and the
+    codebooks), holds bit-identical rotated vectors of its own making; initial nodes, entry list, every batch and the
+    PES verification must then give the same index."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_KEEP_ORDER, FLAG_PERMUTATION_TRANSFORM
+    n, deg, P, efC = 2200, 32, 16, 90
+    w, base, q = _data(1, n)
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric=metric, max_degree=deg, num_subspaces=P, ef_construction=efC,
+                         insert_subbatch=subbatch, seed=71, flags=FLAG_KEEP_ORDER | FLAG_PERMUTATION_TRANSFORM)
+    ex = gix.export()
+    rot = ex["rotation"]
+    assert np.array_equal(np.abs(rot).sum(0), np.ones(w.d)) and np.array_equal(np.abs(rot).sum(1), np.ones(w.d))
+    kw = dict(pes_every=1) if subbatch else dict(max_batch=min(n, 1024))
+    oix = orc.OracleIndex.build(base, wl.COS if metric == "cos" else wl.L2, deg=deg, P=P, efC=efC, rot=rot,
+                                cb=ex["codebooks"], pes=True, **kw)
+    assert np.array_equal(ex["vectors"], oix.vec)
+    assert ex["entry"].tolist() == list(range(1024))
+    _assert_same_index(ex, oix, "build from raw vectors")
