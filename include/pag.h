@@ -78,14 +78,14 @@ typedef struct {
                                   seeded shuffle: for input that is already in random order.  With
                                   insert_subbatch = 1 this is Alg. 1 as printed, one node after another, the
                                   PES buffer of a node verified right after its insertion. */
-#define PAG_FLAG_PERMUTATION_TRANSFORM 32u /* build time: Q is a random signed permutation (a coordinate shuffle with random
-                                  signs) instead of a Haar-distributed rotation.  Still orthogonal, and its products are exact,
-                                  so the stored vectors are the input's values bit for bit; it does not mix coordinates, so
-                                  it suits data that is already isotropic (and comparisons that must not depend on rounding). */
 #define PAG_FLAG_EXACT_TEST_COUNT 16u /* diagnostic, search time: long searches resolve the seen set for every
                                   neighbour before the projection test instead of only for those that pass it,
                                   so that pag_counters.tests counts exactly the unseen neighbours (Sec. 4.2's
                                   gamma = passes / tests).  Results are unchanged; the search is a few % slower. */
+#define PAG_FLAG_PERMUTATION_TRANSFORM 32u /* build time: Q is a random signed permutation (a coordinate shuffle with random
+                                  signs) instead of a Haar-distributed rotation.  Still orthogonal, and its products are exact,
+                                  so the stored vectors are the input's values bit for bit; it does not mix coordinates, so
+                                  it suits data that is already isotropic (and comparisons that must not depend on rounding). */
 
 /*
  * Flat host view of an index (Alg. 1 output: node set, edge set E, inference
