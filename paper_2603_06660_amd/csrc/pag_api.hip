@@ -698,6 +698,9 @@ static int search_impl(pag_index* ix, const float* Q, uint64_t nq, uint32_t K, u
     a.nq = (u32)nq; a.K = K;
     a.out_ids = (long long*)ids; a.out_dists = dists;
     a.out_scale = ix->metric == PAG_L2 ? 1.0f : 0.5f;
+    // A record caught between two states of a reverse-edge pass (its id row can span two cache lines, and a node may
+    // change slots) can show one node twice; the merge needs the keys of a hop distinct.
+    if (ix->concurrent_view) a.flags |= PAG_SEARCH_DISTINCT;
     PAG_HIP(hipEventRecord(ix->ev[0], ix->stream));
     if ((rc = prepare(ix, Q, nq, ix->ws_qrot, ix->ws_tab))) return rc;
     if ((rc = pag_launch_zero_u32(ix->stream, ix->d_qcounter, 1))) return rc;
@@ -808,6 +811,7 @@ extern "C" int pag_searcher_create(const pag_index* ix, void* stream, pag_search
     s->view = *ix;
     pag_index& v = s->view;
     v.stream = (hipStream_t)stream;
+    v.concurrent_view = 1;
     v.ws_qrot = nullptr; v.ws_qrot_cap = 0;
     v.ws_tab = nullptr; v.ws_tab_cap = 0;
     v.ws_norm = nullptr; v.ws_norm_cap = 0;

@@ -20,6 +20,7 @@ typedef uint32_t u32;
 #define PAG_LDS_RING_MAX_B 128  // larger working sets keep R_F / R_T in HBM (the kernel's NW > 2 instantiations)
 #define PAG_MAX_DEG 64      // one neighbour per lane
 #define PAG_MAX_CW 8        // code dwords per neighbour: up to 64 subspaces
+#define PAG_SEARCH_DISTINCT (1u << 30)  // SearchArgs.flags, internal: a hop drops an id that an earlier slot of the record also lists
 #define PAG_STATIC_SCRATCH_BYTES (48u << 20)   // the device array behind pag_search_static, per GPU
 #define PAG_STATIC_QUERY_FLOATS (4ull << 20)    // of which at most 16 MB hold rotated queries, tables and normalised copies
 
@@ -92,6 +93,7 @@ struct pag_index {
     float* cb;       // [P * 16 * dsub]
     u32* entry;      // [n_entry]
     u32 n_entry;
+    u32 concurrent_view;   // a searcher's view: its searches may overlap a pag_insert that rewrites records
     // workspaces (grown on demand, kept between calls)
     float* ws_qrot;  u64 ws_qrot_cap;     // floats
     float* ws_tab;   u64 ws_tab_cap;      // floats

@@ -842,6 +842,15 @@ struct Wave {
                         else if ((u32)lane > pos) Hk = up;
                     }
                 }
+                if (A.flags & PAG_SEARCH_DISTINCT) {
+                    // searches that overlap an insertion: a record read between two states of a reverse-edge pass may
+                    // list one node in two slots; the first slot stands, the merge needs distinct keys
+                    for (u64 m = __ballot(pass); m;) {
+                        const int p = __ffsll((long long)m) - 1;
+                        m &= m - 1;
+                        if (lane > p && id == rdlane(id, p)) { pass = false; cand = false; }
+                    }
+                }
                 const u64 cmask = __ballot(cand);
                 const u64 pmask = __ballot(pass);
                 s_tests += (u32)__popcll(cmask);

@@ -142,14 +142,16 @@ def test_online_insertion(orc, cfg1_small):
     assert (ids == oi).mean() >= 0.999
 
 
-def test_search_while_inserting(orc):
+@pytest.mark.parametrize("deg", [32, 48])
+def test_search_while_inserting(orc, deg):
     """A searcher (own workspaces and stream) answers queries while pag_insert grows the index from
     another host thread (the online setting of Sec. 5.2): every answer is a valid one for the index
     before or after the insertion, and once the insertion is done the searcher, the index's own
-    pag_search and the oracle agree."""
+    pag_search and the oracle agree.  With 48 neighbours the id row of a record spans two cache lines."""
     import threading
     PagIndex = _gpu()
     w = wl.workload(1, n=40000, nq=200)
+    w = w.__class__(**{**w.__dict__, "deg": deg})
     base, q = wl.make(w, "base"), wl.make(w, "query")
     n0 = 20000
     bd = torch.from_numpy(base).cuda()
