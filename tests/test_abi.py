@@ -51,6 +51,17 @@ def test_struct_layouts_match_the_header(tmp_path):
     assert got == want
 
 
+def test_constants_match_the_header():
+    """Flags, metrics and error codes of the binding are the header's."""
+    from paper_2603_06660_amd import binding
+    text = open(HEADER).read()
+    flags = {k: int(v) for k, v in re.findall(r"#define\s+PAG_(FLAG_[A-Z0-9_]+)\s+(\d+)u", text)}
+    assert len(flags) >= 6
+    for name, value in flags.items():
+        assert getattr(binding, name) == value, name
+    assert sorted(flags.values()) == [1 << i for i in range(len(flags))]     # distinct single bits, none skipped
+
+
 def test_argument_errors_need_no_gpu(lib):
     """Null handles and null pointers are rejected before any HIP call."""
     lib.pag_last_error.restype = C.c_char_p
