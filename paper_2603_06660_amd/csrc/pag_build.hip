@@ -65,54 +65,6 @@ __device__ __forceinline__ void dist_lds4(const pag_vecs& V, u32 d, const float*
     for (int g = 0; g < 4; ++g) out[g] = (float)pagk::fold_total<4>(tot, g);
 }
 
-// the same for C staged vectors at once: the four rows are fetched once and used C times
-template <int C>
-__device__ __forceinline__ void dist_lds4xC(const pag_vecs& V, u32 d, const float* s0, const u32 (&id)[4], float (&out)[C][4]) {
-    double acc[C][4];
-#pragma unroll
-    for (int i = 0; i < C; ++i)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) acc[i][g] = 0.0;
-    for (u32 c = threadIdx.x; c < d / 4; c += 64) {
-        float4 b[4];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) b[g] = pag_vload4(V, id[g], c);
-#pragma unroll
-        for (int i = 0; i < C; ++i) {
-            const float4 a = ((const float4*)(s0 + (size_t)i * d))[c];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float dx = a.x - b[g].x, dy = a.y - b[g].y, dz = a.z - b[g].z, dw = a.w - b[g].w;
-                acc[i][g] = __builtin_fma((double)dx, (double)dx, acc[i][g]);
-                acc[i][g] = __builtin_fma((double)dy, (double)dy, acc[i][g]);
-                acc[i][g] = __builtin_fma((double)dz, (double)dz, acc[i][g]);
-                acc[i][g] = __builtin_fma((double)dw, (double)dw, acc[i][g]);
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < C; ++i) {
-        const double t = pagk::fold_sum<4>(acc[i]);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) out[i][g] = (float)pagk::fold_total<4>(t, g);
-    }
-}
-
-// squared distance between two vectors staged in LDS, all lanes get the result
-__device__ __forceinline__ float dist_lds_lds(u32 d, const float* s0, const float* s1) {
-    const float4 *q0 = (const float4*)s0, *q1 = (const float4*)s1;
-    double acc = 0.0;
-    for (u32 c = threadIdx.x; c < d / 4; c += 64) {
-        const float4 a = q0[c], b = q1[c];
-        const float dx = a.x - b.x, dy = a.y - b.y, dz = a.z - b.z, dw = a.w - b.w;
-        acc = __builtin_fma((double)dx, (double)dx, acc);
-        acc = __builtin_fma((double)dy, (double)dy, acc);
-        acc = __builtin_fma((double)dz, (double)dz, acc);
-        acc = __builtin_fma((double)dw, (double)dw, acc);
-    }
-    return (float)wave_sum(acc);
-}
-
 __device__ __forceinline__ void stage(const pag_vecs& V, u32 d, u32 id, float* s, int lane) {
     for (u32 c = lane; c < d / 4; c += 64) ((float4*)s)[c] = pag_vload4(V, id, c);
 }
@@ -165,27 +117,93 @@ __global__ void k_cand_segments(const u32* __restrict__ cand_cnt, u32 m, u32 can
 }
 
 // ---- RobustPrune over R_L of each new node (Eq. 1, alpha = 1) ----
-// cand_sorted: per node the keys collected by the search (dist bits << 32 | id << 1 | visited),
-// sorted ascending by a segmented radix sort over bits 1..63.  Cut to efC, then scanned: a candidate is kept unless an
-// already kept s has ||s - c|| <= ||v - c||.  Writes N_out(v) into v's record and one reverse
-// pair per kept neighbour: key = target << 32 | dist bits, value = v.
-// The kernel is bound by the rows it fetches (a node's kept rows do not stay in any cache while thousands of
-// nodes are pruned at once): candidates are therefore taken C at a time, staged in LDS, so that one pass over
-// the kept rows serves all C.
-template <int C>
-__global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restrict__ recs,
-                                                  pag_layout L, const u32* __restrict__ nodes, u32 m,
-                                                  const u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC,
-                                                  const u64* __restrict__ pes, float* __restrict__ e2,
-                                                  u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
+// cand_sorted: per node the keys collected by the search (dist bits << 32 | id << 1 | visited), sorted ascending by a
+// segmented radix sort over bits 1..63.  Cut to efC, then scanned in order: a candidate is kept unless an already kept
+// s has ||s - c||^2 <= ||v - c||^2.  Writes N_out(v) into v's record and one reverse pair per kept neighbour:
+// key = target << 32 | dist bits, value = v.
+// The kernel is bound by the rows it fetches: while thousands of nodes are pruned at once, a node's kept rows stay in
+// no cache.  Most occlusion tests are decided by the first few neighbours kept (the closest ones), so the first J kept
+// rows stay in LDS, where every later candidate meets them without memory traffic, and the candidates stream through
+// registers, C at a time, NB groups in flight.  Kept rows beyond J are fetched G at a time, for the candidates that
+// the first J did not occlude.  J is small on purpose: the waves that the LDS leaves room for matter more than the
+// rows it holds.  NQ: 16-byte chunks of a row per lane.
+template <int NQ, int C, int G>
+struct PruneRows {
+    const pag_vecs& V;
+    const u32 d4;            // 16-byte chunks per row
+    const int lane;
+    float4* K;               // [J][NQ * 64] kept rows (zero-padded chunks)
+
+    __device__ __forceinline__ void load_row(u32 id, float4 (&r)[NQ]) const {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const u32 c = (u32)lane + 64u * q;
+            r[q] = c < d4 ? pag_vload4(V, id, c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    __device__ __forceinline__ static void accumulate(const float4& a, const float4& b, double& acc) {
+        const float dx = a.x - b.x, dy = a.y - b.y, dz = a.z - b.z, dw = a.w - b.w;
+        acc = __builtin_fma((double)dx, (double)dx, acc);
+        acc = __builtin_fma((double)dy, (double)dy, acc);
+        acc = __builtin_fma((double)dz, (double)dz, acc);
+        acc = __builtin_fma((double)dw, (double)dw, acc);
+    }
+    // squared distances of the C candidate rows to kept row j (LDS); every lane gets all C
+    __device__ __forceinline__ void to_lds_row(const float4 (&rows)[C][NQ], u32 j, float (&out)[C]) const {
+        double acc[C];
+#pragma unroll
+        for (int i = 0; i < C; ++i) acc[i] = 0.0;
+        const float4* kr = K + (size_t)j * (NQ * 64);
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const float4 k = kr[lane + 64 * q];
+#pragma unroll
+            for (int i = 0; i < C; ++i) accumulate(rows[i][q], k, acc[i]);
+        }
+        const double t = pagk::fold_sum<C>(acc);
+#pragma unroll
+        for (int i = 0; i < C; ++i) out[i] = (float)pagk::fold_total<C>(t, i);
+    }
+    // squared distances of the C candidate rows to G rows fetched from memory
+    __device__ __forceinline__ void to_memory_rows(const float4 (&rows)[C][NQ], const u32 (&sid)[G], float (&out)[C][G]) const {
+        float4 kb[G][NQ];
+#pragma unroll
+        for (int g = 0; g < G; ++g) load_row(sid[g], kb[g]);
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            double acc[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) acc[g] = 0.0;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int g = 0; g < G; ++g) accumulate(rows[i][q], kb[g][q], acc[g]);
+            const double t = pagk::fold_sum<G>(acc);
+#pragma unroll
+            for (int g = 0; g < G; ++g) out[i][g] = (float)pagk::fold_total<G>(t, g);
+        }
+    }
+    // squared distance between two candidate rows
+    __device__ __forceinline__ float between(const float4 (&a)[NQ], const float4 (&b)[NQ]) const {
+        double acc = 0.0;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) accumulate(a[q], b[q], acc);
+        return (float)wave_sum(acc);
+    }
+};
+
+template <int NQ, int C, int G, int NB>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 4)))
+k_prune(pag_vecs vec, uint8_t* __restrict__ recs, pag_layout L, const u32* __restrict__ nodes, u32 m,
+            const u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC, u32 J,
+            const u64* __restrict__ pes, float* __restrict__ e2, u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
     extern __shared__ __align__(16) unsigned char smem[];
-    float* sv = (float*)smem;                  // [C][d] candidate vectors
-    u32* kept = (u32*)(sv + (size_t)C * L.d);  // [deg]
     const u32 vi = blockIdx.x;
     if (vi >= m) return;
-    // the sorted list lives in HBM: it is read once, front to back
-    const u64* sorted = cand_sorted + (u64)vi * cand_cap;   // ascending by (dist, id); bit 0 is the visited flag
     const int lane = threadIdx.x;
+    u32* kept = (u32*)(smem + (size_t)J * NQ * 1024);       // [deg]
+    const PruneRows<NQ, C, G> P{vec, L.d / 4, lane, (float4*)smem};
+    const u64* sorted = cand_sorted + (u64)vi * cand_cap;   // ascending by (dist, id); bit 0 is the visited flag
     const u32 v = nodes[vi];
     u32 nc = cand_cnt[vi];
     if (nc > cand_cap) nc = cand_cap;
@@ -193,57 +211,112 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
     u32 nk = 0;
     u32 my_id = PAG_EMPTY;       // lane s holds kept[s]
     u32 my_key = 0;
-    // C candidates at a time: all are tested against the neighbours kept so far with one pass over those rows,
-    // and each additionally against the earlier ones of its group that have just been kept, which is what
-    // testing them one after the other amounts to.
-    for (u32 ci = 0; ci < nc && nk < L.deg; ci += C) {
-        u64 key[C];
+
+    // The sorted keys are read 64 at a time, one per lane, a block ahead of the rows that they name: a row request
+    // never waits for its key.
+    u32 kbase = 0;
+    u64 kcur = (u32)lane < nc ? sorted[lane] : 0ull;
+    u64 knxt = 64u + lane < nc ? sorted[64u + lane] : 0ull;
+    u64 key[NB][C];
+    float4 row[NB][C][NQ];
+    auto fetch = [&](u32 ci, u64 (&gk)[C], float4 (&rows)[C][NQ]) {
+        if (ci >= kbase + 64) {
+            kcur = knxt;
+            kbase += 64;
+            knxt = kbase + 64u + lane < nc ? sorted[kbase + 64u + lane] : 0ull;
+        }
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            const u32 at = (ci + i < nc ? ci + i : nc - 1) - kbase;      // C divides 64: a group lies in one block
+            const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)kcur, (int)at);
+            const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(kcur >> 32), (int)at);
+            gk[i] = ((u64)hi << 32) | lo;
+            P.load_row(lo >> 1, rows[i]);
+        }
+    };
+    // decides the C candidates at positions ci .. of the list, in order
+    auto decide = [&](u32 ci, const u64 (&key)[C], const float4 (&rows)[C][NQ]) {
         u32 cid[C];
         float dv[C];
         bool occ[C];
 #pragma unroll
         for (int i = 0; i < C; ++i) {
-            const bool there = ci + i < nc;
-            key[i] = sorted[there ? ci + i : nc - 1];
             cid[i] = (u32)(key[i] & 0xFFFFFFFFull) >> 1;
             dv[i] = __uint_as_float((u32)(key[i] >> 32));
             // a node that is searched for a second time finds itself: never its own neighbour
-            occ[i] = !there || cid[i] == v;
-            stage(vec, L.d, cid[i], sv + (size_t)i * L.d, lane);
+            occ[i] = !(ci + i < nc) || cid[i] == v;
         }
-        __syncthreads();
-        for (u32 s0 = 0; s0 < nk; s0 += 4) {
+        const u32 in_lds = nk < J ? nk : J;
+        for (u32 j = 0; j < in_lds; ++j) {
             bool all = true;
 #pragma unroll
             for (int i = 0; i < C; ++i) all = all && occ[i];
             if (all) break;
-            u32 sid[4];
-            float dd[C][4];
+            float dd[C];
+            P.to_lds_row(rows, j, dd);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) sid[g] = kept[s0 + g < nk ? s0 + g : nk - 1];   // a repeated last entry changes nothing
-            dist_lds4xC<C>(vec, L.d, sv, sid, dd);
+            for (int i = 0; i < C; ++i) occ[i] = occ[i] || dd[i] <= dv[i];
+        }
+        for (u32 s0 = J; s0 < nk; s0 += G) {
+            bool all = true;
+#pragma unroll
+            for (int i = 0; i < C; ++i) all = all && occ[i];
+            if (all) break;
+            u32 sid[G];
+            float dd[C][G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) sid[g] = kept[s0 + g < nk ? s0 + g : nk - 1];   // a repeated last entry changes nothing
+            P.to_memory_rows(rows, sid, dd);
 #pragma unroll
             for (int i = 0; i < C; ++i)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) occ[i] = occ[i] || dd[i][g] <= dv[i];
+                for (int g = 0; g < G; ++g) occ[i] = occ[i] || dd[i][g] <= dv[i];
         }
         bool kept_here[C];
+        bool wrote = false;
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             kept_here[i] = false;
             if (nk < L.deg) {
 #pragma unroll
                 for (int j = 0; j < i; ++j)
-                    if (kept_here[j] && !occ[i]) occ[i] = dist_lds_lds(L.d, sv + (size_t)j * L.d, sv + (size_t)i * L.d) <= dv[i];
+                    if (kept_here[j] && !occ[i]) occ[i] = P.between(rows[j], rows[i]) <= dv[i];
                 if (!occ[i]) {
                     if ((u32)lane == nk) { my_id = cid[i]; my_key = (u32)(key[i] >> 32); kept[nk] = cid[i]; }
+                    if (nk < J) {
+                        float4* kr = P.K + (size_t)nk * (NQ * 64);
+#pragma unroll
+                        for (int q = 0; q < NQ; ++q) kr[lane + 64 * q] = rows[i][q];
+                    }
                     nk++;
                     kept_here[i] = true;
+                    wrote = true;
                 }
             }
         }
-        __syncthreads();
+        if (wrote) __syncthreads();      // one wave per workgroup: orders the LDS writes before the next reads
+    };
+
+    // NB groups of C rows are in flight: a buffer is refilled as soon as its group is decided
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+        if ((u32)(b * C) < nc) fetch(b * C, key[b], row[b]);
+    for (u32 ci = 0; ci < nc && nk < L.deg; ci += NB * C) {
+        bool done = false;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const u32 c0 = ci + b * C;
+            if (!done) {
+                if (c0 >= nc || nk >= L.deg) done = true;
+                else {
+                    decide(c0, key[b], row[b]);
+                    if (c0 + NB * C < nc) fetch(c0 + NB * C, key[b], row[b]);
+                }
+            }
+        }
+        if (done) break;
     }
+    __syncthreads();
     u32* ids = (u32*)(recs + (u64)v * L.rec_bytes);
     if ((u32)lane < L.deg) {
         ids[lane] = my_id;
@@ -270,6 +343,23 @@ __global__ void __launch_bounds__(64) k_prune_new(pag_vecs vec, uint8_t* __restr
             rev_vals[o2] = v;
         }
     }
+}
+
+template <int NQ>
+static int launch_prune(hipStream_t s, const pag_index* ix, const u32* nodes, u32 m, const u64* cand_sorted,
+                        const u32* cand_cnt, u32 cand_cap, const u64* pes, u64* rev_keys, u32* rev_vals) {
+    const pag_layout& L = ix->L;
+    // kept rows held in LDS (slots of NQ KB): four, more while they fit 16 KB, fewer beyond 36 KB.  Measured on
+    // 1M x 768 / 1024 / 1536 and 250k x 3072: 16 / 16 / 24 / 36 KB are the fastest; larger sets lose more waves than
+    // they save reads.
+    u32 J = std::max<u32>(4u, 16u / NQ);
+    J = std::min<u32>(J, 36u / NQ);
+    J = std::min<u32>(J, L.deg);
+    const u32 lds = J * NQ * 1024u + L.deg * 4;
+    hipLaunchKernelGGL((k_prune<NQ, 2, 2, 2>), dim3(m), dim3(64), lds, s, pag_vecs_of(ix), ix->rec, L, nodes, m, cand_sorted,
+                       cand_cnt, cand_cap, ix->efC, J, pes, ix->e2, rev_keys, rev_vals);
+    PAG_HIP(hipGetLastError());
+    return PAG_OK;
 }
 
 // ---- reverse edges, one wave per target (Sec. 2.1, N_in(v); Eq. 1) ----
@@ -592,18 +682,17 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         if ((rc = search_candidates(ix, ws, ix->ws_qrot, m, b, cand_cap, n_end))) return rc;
         //    RobustPrune -> N_out(v), reverse pairs
         {
-            // four candidates per pass over the kept rows where their staging fits 16 KB of LDS per wave (about a tenth
-            // faster there), else two: with longer rows the lost occupancy cancels the saved reads
-            if (4u * L.d * 4 <= 16384u) {
-                const u32 plds = 4 * L.d * 4 + L.deg * 4;
-                hipLaunchKernelGGL(k_prune_new<4>, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, nodes, (u32)m,
-                                   ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ix->e2, ws.rk_in, ws.rv_in);
-            } else {
-                const u32 plds = 2 * L.d * 4 + L.deg * 4;
-                hipLaunchKernelGGL(k_prune_new<2>, dim3((unsigned)m), dim3(64), plds, s, pag_vecs_of(ix), ix->rec, L, nodes, (u32)m,
-                                   ws.cand_sorted, ws.cand_cnt, cand_cap, ix->efC, ws.pes, ix->e2, ws.rk_in, ws.rv_in);
-            }
-            PAG_HIP(hipGetLastError());
+#define PRUNE_ARGS s, ix, nodes, (u32)m, ws.cand_sorted, ws.cand_cnt, cand_cap, ws.pes, ws.rk_in, ws.rv_in
+            const u32 nq = (L.d / 4 + 63) / 64;          // 16-byte chunks of a row per lane
+            if (nq <= 1) rc = launch_prune<1>(PRUNE_ARGS);
+            else if (nq == 2) rc = launch_prune<2>(PRUNE_ARGS);
+            else if (nq == 3) rc = launch_prune<3>(PRUNE_ARGS);
+            else if (nq == 4) rc = launch_prune<4>(PRUNE_ARGS);
+            else if (nq <= 6) rc = launch_prune<6>(PRUNE_ARGS);
+            else if (nq <= 8) rc = launch_prune<8>(PRUNE_ARGS);
+            else rc = launch_prune<12>(PRUNE_ARGS);
+#undef PRUNE_ARGS
+            if (rc) return rc;
         }
         PAG_HIP(hipEventRecord(ws.ev[2], s));
         // 4. group reverse pairs by target
