@@ -66,16 +66,18 @@ def _assert_same_index(got, oix, what):
         assert (got[k][:n] == getattr(oix, k)).mean() >= 0.999, k
 
 
-def _oracle_on(orc, ex, order, base, **kw):
+def _oracle_on(orc, ex, order, base, check_rotation=True, **kw):
     """The oracle's construction over the index's rotated vectors taken in insertion order.  The vectors are
     the exported ones, checked first against the oracle's own rotation of the raw data (the two agree in all
     but a few last bits; construction is chaotic in those, so both sides must start from the same values)."""
     vec = ex["vectors"][order]
-    raw = base[order[:200]]
-    if ex["metric"] == wl.COS:
-        raw = raw / np.linalg.norm(raw.astype(np.float64), axis=1, keepdims=True).astype(np.float32)
-    ref = np.stack([orc.rotate(ex["rotation"], x) for x in raw])
-    assert (ref == vec[:200]).mean() >= 0.999 and np.allclose(ref, vec[:200], rtol=1e-5, atol=1e-6)
+    if check_rotation:
+        raw = base[order[:200]]
+        if ex["metric"] == wl.COS:
+            r64 = raw.astype(np.float64)      # x / ||x|| in fp64, rounded once: the oracle's normalisation
+            raw = (r64 / np.sqrt((r64 * r64).sum(axis=1, keepdims=True))).astype(np.float32)
+        ref = np.stack([orc.rotate(ex["rotation"], x) for x in raw])
+        assert (ref == vec[:200]).mean() >= 0.999 and np.allclose(ref, vec[:200], rtol=1e-5, atol=1e-6)
     return orc.OracleIndex.build(vec, wl.L2, rot=np.eye(vec.shape[1], dtype=np.float32), cb=ex["codebooks"], **kw)
 
 
@@ -266,6 +268,38 @@ def test_small_and_extreme_shapes(orc, n, d, P, deg, efC, subbatch):
     oix = _oracle_on(orc, ex, np.arange(n), base, deg=deg, P=P, efC=efC, pes=True, **kw)
     _assert_same_index(ex, oix, "shape n=%d d=%d" % (n, d))
     assert ex["entry"].tolist() == list(range(n))
+
+
+@pytest.mark.parametrize("d,P,deg,efC,metric,half", [
+    (96, 12, 40, 90, "l2", False),       # one 16-byte chunk per lane, half the lanes idle; more neighbours kept than LDS rows
+    (384, 16, 32, 80, "ip", False),      # two chunks per lane
+    (640, 20, 24, 70, "l2", False),      # three, ragged
+    (1024, 32, 48, 110, "cos", False),   # four
+    (1280, 40, 36, 60, "l2", False),     # five of six
+    (2048, 64, 32, 60, "ip", False),     # eight
+    (2560, 40, 20, 50, "l2", False),     # ten of twelve
+    (768, 32, 32, 100, "l2", True),      # the 16-bit vector store
+])
+def test_every_row_length_class(orc, d, P, deg, efC, metric, half):
+    """Construction in the default batches at one row length per instantiation of the pruning kernel (16-byte
+    chunks per lane: 1, 2, 3, 4, 6, 8, 12), on isotropic data, where RobustPrune keeps more neighbours than the
+    kernel holds in LDS: both of its paths (kept rows in LDS, kept rows from memory) decide as the oracle does."""
+    PagIndex = _gpu()
+    from paper_2603_06660_amd import FLAG_FP16_VECTORS, FLAG_KEEP_ORDER
+    n = 520
+    rng = np.random.default_rng(7000 + d)
+    base = rng.standard_normal((n, d)).astype(np.float32)
+    if metric == "ip":
+        base /= np.linalg.norm(base, axis=1, keepdims=True)
+    gix = PagIndex.build(torch.from_numpy(base).cuda(), metric=metric, max_degree=deg, num_subspaces=P,
+                         ef_construction=efC, seed=73, flags=FLAG_KEEP_ORDER | (FLAG_FP16_VECTORS if half else 0))
+    ex = gix.export()
+    # with the 16-bit store the index is the rounded data: the oracle starts from the exported values as they are
+    oix = _oracle_on(orc, ex, np.arange(n), base, check_rotation=not half, deg=deg, P=P, efC=efC, pes=True,
+                     max_batch=min(n, 1024))
+    _assert_same_index(ex, oix, "row length d=%d" % d)
+    kept = (ex["adj"] != orc.EMPTY).sum(axis=1)
+    assert kept.max() > 16 or deg <= 16        # beyond the rows held in LDS at every length
 
 
 def test_duplicated_vectors(orc):
