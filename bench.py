@@ -222,6 +222,8 @@ def search_workload(args, w, wl, torch, np, PagIndex, *, steps, warmup, efs_fixe
                 "kernel": "pagk::k_search", "kernel_ms": round(t["kernel_ms"], 4),
                 "kernel_ms_median": round(t["kernel_ms_median"], 4), "prepare_ms": round(t["prepare_ms"], 4),
                 "algorithmic_bytes_per_launch": int(t["bytes_per_launch"]),
+                # secondary: table additions of the screen (hops x neighbours x subspaces) + 3 d per exact distance
+                "alu_TFLOPs": round((c["hops"] * w.deg * w.P + c["exact"] * 3 * w.d) / steps / (t["kernel_ms"] * 1e-3) / 1e12, 2),
                 "measured_row_read_GBps": {"in_order": round(stream_gbs, 1), "scattered": round(gather_gbs, 1),
                                            "scattered_with_hop_side_traffic": round(hop_gbs, 1)},
                 "frac_of_measured_scattered_reads": round(t["achieved"] / gather_gbs, 4),
