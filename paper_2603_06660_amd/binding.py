@@ -150,6 +150,22 @@ class PagIndex:
             _check(lib.pag_import(C.byref(arr), C.byref(p), C.byref(h)), "pag_import")
         return cls(h, torch.device(device))
 
+    def save(self, path):
+        """Writes the arrays of pag_export into one uncompressed .npz file."""
+        ex = self.export()
+        with open(path, "wb") as f:
+            np.savez(f, **ex)
+
+    @classmethod
+    def load(cls, path, **kw):
+        """pag_import of a file written by save().  Keyword arguments as for from_arrays: what an index file does
+        not hold (ef_construction, search_b, flags, capacity, seed, stream, device, insert_subbatch)."""
+        names = {v: k for k, v in _METRICS.items()}
+        with np.load(path, allow_pickle=False) as z:
+            arrays = {k: z[k] for k in ("vectors", "adj", "a", "c", "e2", "codes", "rotation", "codebooks", "entry")}
+            metric = names[int(z["metric"])]
+        return cls.from_arrays(metric=metric, **arrays, **kw)
+
     def close(self):
         if self._h is not None and self._h.value:
             load_library().pag_free(self._h)

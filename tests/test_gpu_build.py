@@ -389,3 +389,25 @@ def test_index_grown_from_a_few_vectors(orc, cfg1_small):
     assert len(set(ent.tolist())) == len(ent) == 1024 and ent.max() < n
     oi, od, _ = _oracle_view(orc, ex).search(q, w.K, 64)
     assert (ids.cpu().numpy() == oi).mean() >= 0.999
+
+
+def test_save_and_load(orc, cfg1_small, tmp_path):
+    """An index written to a file and read back answers as before and keeps growing as before."""
+    PagIndex = _gpu()
+    w, base, q, _, _ = cfg1_small
+    n0 = 2000
+    bd, qd = torch.from_numpy(base).cuda(), torch.from_numpy(q).cuda()
+    kw = dict(metric="l2", max_degree=w.deg, num_subspaces=w.P, ef_construction=100, seed=5, capacity=len(base))
+    gix = PagIndex.build(bd[:n0].contiguous(), **kw)
+    i0, d0 = gix.search(qd, w.K, 64)
+    path = tmp_path / "index.npz"
+    gix.save(path)
+    hix = PagIndex.load(path, ef_construction=100, seed=5, capacity=len(base))
+    i1, d1 = hix.search(qd, w.K, 64)
+    assert torch.equal(i0, i1) and torch.equal(d0, d1)
+    extra = bd[n0:].contiguous()
+    gix.insert(extra)
+    hix.insert(extra)
+    a, b = gix.export(), hix.export()
+    for k in ("vectors", "adj", "a", "c", "e2", "codes", "entry"):
+        assert np.array_equal(a[k], b[k]), k
