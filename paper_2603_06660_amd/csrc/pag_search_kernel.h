@@ -227,6 +227,8 @@ struct Wave {
     u64 wmax;                       // BIG: key of W's farthest member, valid while nW == b
     u64 nx_key;                     // BIG: key of the node to expand next (PAG_KEY_INVALID: W has no unvisited node)
     bool nx_known;                  // BIG: nx_key is up to date
+    u64 GM, GU;                     // BIG: lane s < NW holds slot s's farthest member (0: slot empty) and its closest
+                                    // unvisited member (PAG_KEY_INVALID: none); the other lanes hold 0 / PAG_KEY_INVALID
     float4 q[QV];
     u64 W[NW];
     u64 RL[NW > 2 ? 1 : NW];        // unused for large working sets: their R_L is SA[0, nRL)
@@ -566,32 +568,54 @@ struct Wave {
     // member and the replacement of that one; the order of the rest matters at the round's end alone, where
     // everything is sorted anyway.
 
-    // key of the closest unvisited member of W (PAG_KEY_INVALID if there is none)
-    __device__ __forceinline__ u64 min_unvisited() const {
-        u64 m = PAG_KEY_INVALID;
-#pragma unroll
-        for (int s = 0; s < NW; ++s) {
-            const u32 idx = s * 64 + lane;
-            const u64 k = (idx < nW && !(W[s] & 1ull)) ? W[s] : PAG_KEY_INVALID;
-            m = k < m ? k : m;
-        }
-        return wave_extreme<false>(m);
+    // Keys are distance bits over (id << 1 | visited): an extreme key is found in two 32-bit steps -- the extreme
+    // distance, then the extreme low word among the members at that distance -- each a handful of DPP
+    // instructions, where a 64-bit reduction moves and compares register pairs.
+    // W's slots (one register per lane each) keep their extremes in GM / GU, so that finding W's farthest member or
+    // its closest unvisited one is a reduction over NW <= 16 lanes, and a change of one member costs a reduction over
+    // that member's slot alone, reached through a uniform branch.
+
+    // farthest member of slot S (0 if the slot is empty)
+    template <int S>
+    __device__ __forceinline__ u64 slot_max() const {
+        const bool valid = (u32)(S * 64 + lane) < nW;
+        const u32 hi = valid ? (u32)(W[S] >> 32) : 0u;
+        const u32 mh = wave_extreme_u32<true>(hi);
+        const u32 lo = (valid && hi == mh) ? (u32)W[S] : 0u;
+        return ((u64)mh << 32) | wave_extreme_u32<true>(lo);
     }
 
-    __device__ __forceinline__ u64 max_member() const {
-        u64 m = 0;
-#pragma unroll
-        for (int s = 0; s < NW; ++s) {
-            const u32 idx = s * 64 + lane;
-            const u64 k = idx < nW ? W[s] : 0ull;
-            m = k > m ? k : m;
+    // closest unvisited member of slot S (PAG_KEY_INVALID if there is none)
+    template <int S>
+    __device__ __forceinline__ u64 slot_min_unvisited() const {
+        const bool ok = (u32)(S * 64 + lane) < nW && !(W[S] & 1ull);
+        const u32 hi = ok ? (u32)(W[S] >> 32) : 0xFFFFFFFFu;
+        const u32 mh = wave_extreme_u32<false>(hi);
+        const u32 lo = (ok && hi == mh) ? (u32)W[S] : 0xFFFFFFFFu;      // distances are finite: no member carries mh = ~0
+        return ((u64)mh << 32) | wave_extreme_u32<false>(lo);
+    }
+
+    // extreme over the slots: lanes 0 .. NW - 1 of GM (MAX) or GU
+    template <bool MAX>
+    __device__ __forceinline__ u64 over_slots(u64 v) const {
+        const u32 neutral = MAX ? 0u : 0xFFFFFFFFu;
+        const u32 mh = row0_extreme_u32<MAX>((u32)(v >> 32));
+        const u32 lo = (u32)(v >> 32) == mh ? (u32)v : neutral;
+        return ((u64)mh << 32) | row0_extreme_u32<MAX>(lo);
+    }
+
+    // runs f(slot) for the one slot g (uniform), with the slot number as a compile-time constant
+    template <int S = 0, class F>
+    __device__ __forceinline__ void at_slot(int g, F&& f) {
+        if constexpr (S < NW) {
+            if (g == S) f(std::integral_constant<int, S>{});
+            else at_slot<S + 1>(g, f);
         }
-        return wave_extreme<true>(m);
     }
 
     // finds the node that will be expanded next and requests its adjacency record
     __device__ __forceinline__ void look_ahead() {
-        nx_key = min_unvisited();
+        nx_key = over_slots<false>(GU);
         nx_known = true;
         nx_id = PAG_EMPTY;
         if (nx_key != PAG_KEY_INVALID) {
@@ -640,20 +664,25 @@ struct Wave {
             const int src = __ffsll((long long)__ballot(pass && cP == j)) - 1;
             const u64 k = rdlane64(pk, src);
             if (nW < b) {
-                const u32 slot = nW >> 6, ln = nW & 63u;
-#pragma unroll
-                for (int s = 0; s < NW; ++s)
-                    if ((u32)s == slot && (u32)lane == ln) W[s] = k;
+                const int slot = (int)(nW >> 6), ln = (int)(nW & 63u);
+                at_slot(slot, [&](auto S_) { constexpr int S = decltype(S_)::value; if (lane == ln) W[S] = k; });
+                if (lane == slot) { GM = k > GM ? k : GM; GU = k < GU ? k : GU; }
                 nW++;
-                if (nW == b) wmax = max_member();
+                if (nW == b) wmax = over_slots<true>(GM);
             } else if (k < wmax) {
-                // the farthest member leaves for R_T (pushes of one hop: farthest first), the passer takes its slot
+                // the farthest member leaves for R_T (pushes of one hop: farthest first), the passer takes its place
                 if (lane == 0) RT[(hdT + n_ej) & A.ring_mask] = wmax;
                 n_ej++;
-#pragma unroll
-                for (int s = 0; s < NW; ++s)
-                    if ((W[s] | 1ull) == (wmax | 1ull)) W[s] = k;
-                wmax = max_member();
+                const int g = __ffsll((long long)__ballot(GM == wmax)) - 1;       // its slot
+                at_slot(g, [&](auto S_) {
+                    constexpr int S = decltype(S_)::value;
+                    if (W[S] == wmax) W[S] = k;
+                    const u64 m = slot_max<S>();
+                    if (lane == S) GM = m;
+                });
+                // the slot's closest unvisited member: the one that left was it only if it was the slot's last
+                if (lane == g) GU = (GU == wmax) ? k : (k < GU ? k : GU);
+                wmax = over_slots<true>(GM);
             } else {
                 break;
             }
@@ -711,6 +740,7 @@ struct Wave {
             Hk = PAG_KEY_INVALID;
             nx_id = PAG_EMPTY;
             wmax = 0; nx_key = PAG_KEY_INVALID; nx_known = false;
+            GM = 0ull; GU = PAG_KEY_INVALID;
             __syncthreads();
         }
         s_queries++;
@@ -736,14 +766,19 @@ struct Wave {
                 // closest unvisited member of W
                 u64 ukey = 0;
                 if constexpr (BIG) {
-                    if (!nx_known) nx_key = min_unvisited();
+                    if (!nx_known) nx_key = over_slots<false>(GU);
                     nx_known = false;
                     if (nx_key == PAG_KEY_INVALID) break;
                     PAG_MARK(5);
                     ukey = nx_key;
-#pragma unroll
-                    for (int s = 0; s < NW; ++s)
-                        if (W[s] == ukey) W[s] |= 1ull;
+                    const int g = __ffsll((long long)__ballot(GU == ukey)) - 1;        // its slot
+                    at_slot(g, [&](auto S_) {
+                        constexpr int S = decltype(S_)::value;
+                        if (W[S] == ukey) W[S] |= 1ull;
+                        const u64 m = slot_min_unvisited<S>();
+                        if (lane == S) GU = m;
+                    });
+                    if (GM == ukey) GM |= 1ull;                                         // it may be its slot's farthest too
                     if (nW == b && (wmax | 1ull) == (ukey | 1ull)) wmax |= 1ull;
                 } else {
                     int us = -1, ul = 0;
@@ -923,13 +958,20 @@ struct Wave {
                     const u32 idx = s * 64 + lane;
                     W[s] = idx < nW ? x[s] : PAG_KEY_INVALID;
                 }
-                wmax = 0ull;
-                if (nW == b) {                                   // key b - 1 of the sorted list
-                    const u32 wr = b - 1;
+                // W is sorted now: a slot's farthest member is its last, its closest unvisited one the first unvisited
+                GM = 0ull; GU = PAG_KEY_INVALID;
 #pragma unroll
-                    for (int s = 0; s < NW; ++s)
-                        if ((int)(wr >> 6) == s) wmax = rdlane64(x[s], wr & 63);
+                for (int s = 0; s < NW; ++s) {
+                    const u32 first = s * 64;
+                    if (nW > first) {
+                        const u32 cnt = nW - first < 64u ? nW - first : 64u;
+                        const u64 far = rdlane64(W[s], (int)cnt - 1);
+                        const u64 open = __ballot((u32)lane < cnt && !(W[s] & 1ull));
+                        const u64 near = open ? rdlane64(W[s], __ffsll((long long)open) - 1) : PAG_KEY_INVALID;
+                        if (lane == s) { GM = far; GU = near; }
+                    }
                 }
+                wmax = nW == b ? over_slots<true>(GM) : 0ull;
                 nx_known = false;
                 const u32 rest = n - nW;                         // <= b; written worst first
 #pragma unroll

@@ -1,5 +1,5 @@
-// Wave-wide sums of per-lane fp64 partials on gfx950 (64 lanes): DPP within rows of 16 lanes,
-// lane-swap instructions across rows.  No LDS traffic.
+// Wave-wide sums of per-lane fp64 partials and extremes of 32-bit values on gfx950 (64 lanes): DPP within rows of
+// 16 lanes, lane-swap instructions or scalar registers across rows.  No LDS traffic.
 #pragma once
 
 #include "pag_internal.h"
@@ -71,31 +71,38 @@ __device__ __forceinline__ double fold_total(double tot, int g) {
                             __builtin_amdgcn_readlane(__double2loint(tot), src));
 }
 
-// Wave-wide minimum / maximum of one 64-bit key per lane, result in every lane: four DPP steps
-// within the rows of 16 lanes, two exchanges across the rows.
-template <int CTRL>
-__device__ __forceinline__ u64 dpp_move_u64(u64 x) {
-    int lo = (int)(u32)x, hi = (int)(u32)(x >> 32);
-    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, false);
-    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, false);
-    return ((u64)(u32)hi << 32) | (u32)lo;
-}
-
+// Wave-wide minimum / maximum of one 32-bit value per lane: four DPP steps leave every row of 16 lanes with its
+// extreme, the four rows are then combined through scalar registers.  The result is uniform.
 template <bool MAX>
-__device__ __forceinline__ u64 pick(u64 a, u64 b) {
+__device__ __forceinline__ u32 pick32(u32 a, u32 b) {
     if constexpr (MAX) return a > b ? a : b;
     else return a < b ? a : b;
 }
 
+template <int CTRL>
+__device__ __forceinline__ u32 dpp_move_u32(u32 x) {
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
+}
+
 template <bool MAX>
-__device__ __forceinline__ u64 wave_extreme(u64 x) {
-    x = pick<MAX>(x, dpp_move_u64<0xB1>(x));     // quad_perm [1,0,3,2]
-    x = pick<MAX>(x, dpp_move_u64<0x4E>(x));     // quad_perm [2,3,0,1]
-    x = pick<MAX>(x, dpp_move_u64<0x141>(x));    // row_half_mirror
-    x = pick<MAX>(x, dpp_move_u64<0x140>(x));    // row_mirror
-    x = pick<MAX>(x, (u64)__shfl_xor((unsigned long long)x, 16, 64));
-    x = pick<MAX>(x, (u64)__shfl_xor((unsigned long long)x, 32, 64));
-    return x;
+__device__ __forceinline__ u32 wave_extreme_u32(u32 x) {
+    x = pick32<MAX>(x, dpp_move_u32<0xB1>(x));     // quad_perm [1,0,3,2]
+    x = pick32<MAX>(x, dpp_move_u32<0x4E>(x));     // quad_perm [2,3,0,1]
+    x = pick32<MAX>(x, dpp_move_u32<0x141>(x));    // row_half_mirror
+    x = pick32<MAX>(x, dpp_move_u32<0x140>(x));    // row_mirror
+    const u32 r0 = (u32)__builtin_amdgcn_readlane((int)x, 0), r1 = (u32)__builtin_amdgcn_readlane((int)x, 16);
+    const u32 r2 = (u32)__builtin_amdgcn_readlane((int)x, 32), r3 = (u32)__builtin_amdgcn_readlane((int)x, 48);
+    return pick32<MAX>(pick32<MAX>(r0, r1), pick32<MAX>(r2, r3));
+}
+
+// The same over lanes 0 .. 15 only: the extreme of row 0 (the other rows take no part), uniform.
+template <bool MAX>
+__device__ __forceinline__ u32 row0_extreme_u32(u32 x) {
+    x = pick32<MAX>(x, dpp_move_u32<0xB1>(x));
+    x = pick32<MAX>(x, dpp_move_u32<0x4E>(x));
+    x = pick32<MAX>(x, dpp_move_u32<0x141>(x));
+    x = pick32<MAX>(x, dpp_move_u32<0x140>(x));
+    return (u32)__builtin_amdgcn_readlane((int)x, 0);
 }
 
 }  // namespace pagk
