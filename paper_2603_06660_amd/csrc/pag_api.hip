@@ -302,7 +302,7 @@ extern "C" int pag_free(pag_index* ix) {
     DeviceGuard g(ix->device);
     (void)hipStreamSynchronize(ix->stream);
     void* ptrs[] = { ix->vec, ix->rec, ix->e2, ix->rot, ix->cb, ix->entry, ix->ws_qrot, ix->ws_tab, ix->ws_norm,
-                     ix->ws_bitmap, ix->ws_rings, ix->d_qcounter, ix->d_counters };
+                     ix->ws_bitmap, ix->ws_rings, ix->ws_order, ix->d_qcounter, ix->d_counters };
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (auto& e : ix->ev) if (e) (void)hipEventDestroy(e);
     delete ix;
@@ -703,6 +703,8 @@ static int search_impl(pag_index* ix, const float* Q, uint64_t nq, uint32_t K, u
     if (ix->concurrent_view) a.flags |= PAG_SEARCH_DISTINCT;
     PAG_HIP(hipEventRecord(ix->ev[0], ix->stream));
     if ((rc = prepare(ix, Q, nq, ix->ws_qrot, ix->ws_tab))) return rc;
+    // more queries than resident waves: those that run side by side are chosen to be neighbours
+    if (nq > (u64)grid && (rc = pag_order_queries(ix, ix->ws_qrot, nq, &a.order))) return rc;
     if ((rc = pag_launch_zero_u32(ix->stream, ix->d_qcounter, 1))) return rc;
     PAG_HIP(hipEventRecord(ix->ev[1], ix->stream));
     if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
@@ -795,7 +797,7 @@ struct pag_searcher {
 
 static void searcher_release(pag_searcher* s) {
     pag_index& v = s->view;
-    void* ptrs[] = { v.ws_qrot, v.ws_tab, v.ws_norm, v.ws_bitmap, v.ws_rings, v.d_qcounter, v.d_counters };
+    void* ptrs[] = { v.ws_qrot, v.ws_tab, v.ws_norm, v.ws_bitmap, v.ws_rings, v.ws_order, v.d_qcounter, v.d_counters };
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (auto& e : v.ev) if (e) (void)hipEventDestroy(e);
     delete s;
@@ -817,6 +819,7 @@ extern "C" int pag_searcher_create(const pag_index* ix, void* stream, pag_search
     v.ws_norm = nullptr; v.ws_norm_cap = 0;
     v.ws_bitmap = nullptr; v.ws_bitmap_cap = 0;
     v.ws_rings = nullptr; v.ws_rings_cap = 0;
+    v.ws_order = nullptr; v.ws_order_cap = 0;
     v.d_qcounter = nullptr; v.d_counters = nullptr;
     for (auto& e : v.ev) e = nullptr;
     v.last_search_ms = v.last_prepare_ms = v.last_build_ms = 0.0;

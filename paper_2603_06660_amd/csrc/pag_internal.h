@@ -100,6 +100,7 @@ struct pag_index {
     float* ws_norm;  u64 ws_norm_cap;     // floats (normalised copies for COS)
     u32* ws_bitmap;  u64 ws_bitmap_cap;   // u32 words: per-wave seen-set spill bitmaps
     u64* ws_rings;   u64 ws_rings_cap;    // u64 keys: per-wave R_F / R_T / R_L of large working sets
+    u32* ws_order;   u64 ws_order_cap;    // u32 words: workspace of pag_order_queries
     u32* d_qcounter;                      // persistent-wave work counter
     u64* d_counters;                      // CTR_COUNT
     hipEvent_t ev[4];
@@ -130,6 +131,7 @@ struct SearchArgs {
     u32* cand_cnt;           // [nq]
     u32 cand_cap;
     u64* pes;                // [nq * deg] indexing mode: PES buffer H(v), ascending keys, PAG_KEY_INVALID = empty; null = off
+    const u32* order;        // [nq] the order in which the waves take the queries (null: as numbered)
     u32* qcounter;
     u64* counters;
     u32* bitmap;             // [grid * bitmap_words]
@@ -145,6 +147,9 @@ int pag_launch_rotate(hipStream_t s, const float* X, u64 rows, u32 d, const floa
 int pag_launch_tables(hipStream_t s, const float* qrot, u64 rows, const pag_layout& L, const float* cb, float* tables);
 int pag_launch_normalise(hipStream_t s, const float* X, u64 rows, u32 d, float* out);
 int pag_launch_zero_u32(hipStream_t s, u32* p, u64 count);
+// The order in which a batch of rotated queries is best taken (queries that run side by side should search the same
+// part of the graph); *order points into ix->ws_order.  Allocates (grows ix->ws_order).
+int pag_order_queries(pag_index* ix, const float* qrot, u64 nq, const u32** order);
 int pag_launch_convert(hipStream_t s, const void* src, u32 src_half, void* dst, u32 dst_half, u64 count);   // float <-> __half, round to nearest even
 int pag_launch_exact(hipStream_t s, const pag_index* ix, const float* qrot, u64 nq, const u32* ids, u32 m, float* keys);
 int pag_launch_screen(hipStream_t s, const pag_index* ix, const float* tables, u64 nq, const u32* u, const float* Du, float* est);

@@ -3,6 +3,11 @@
 // (Alg. 2, projection-table step).  All sums are fp64 sums of exact fp32 x fp32 products,
 // rounded once to fp32, so that they agree with a plain fp64 evaluation to the last bit in all
 // but a vanishing fraction of the outputs.
+#include <hipcub/hipcub.hpp>
+
+#include <algorithm>
+#include <string>
+
 #include "pag_internal.h"
 
 namespace {
@@ -122,7 +127,130 @@ __global__ void __launch_bounds__(256) k_zero_u32(u32* p, u64 count) {
     if (i < count) p[i] = 0u;
 }
 
+// ---------------------------------------------------------------------------------------
+// Query order.  The waves take the queries of a batch a few thousand at a time; when the queries that run side by
+// side search the same part of the graph, part of their rows comes from the memory-side cache instead of HBM.  The
+// batch is therefore taken in the order of its projections onto one direction: of ORDER_CAND stored vectors (the
+// first entry nodes, i.e. random data points), the one along which the batch varies most.  Results do not depend
+// on the order.
+// ---------------------------------------------------------------------------------------
+constexpr u32 ORDER_CAND = 16;
+
+// dirs[k] = stored vector of entry[k] as fp32, norm2[k] = its squared length
+__global__ void __launch_bounds__(64) k_order_dirs(pag_vecs vec, const u32* __restrict__ entry, float* __restrict__ dirs,
+                                                   float* __restrict__ norm2) {
+    const u32 k = blockIdx.x, d = vec.d;
+    const u32 id = entry[k];
+    float acc = 0.f;
+    for (u32 c = threadIdx.x; c < d / 4; c += 64) {
+        const float4 x = pag_vload4(vec, id, c);
+        ((float4*)(dirs + (u64)k * d))[c] = x;
+        acc += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (threadIdx.x == 0) norm2[k] = acc;
+}
+
+// proj[row][k] = <q_row, dirs[k]>, one wave per row
+__global__ void __launch_bounds__(64) k_order_project(const float* __restrict__ qrot, u64 rows, u32 d, const float* __restrict__ dirs,
+                                                      u32 ncand, float* __restrict__ proj) {
+    const u64 row = blockIdx.x;
+    if (row >= rows) return;
+    const int lane = threadIdx.x;
+    float acc[ORDER_CAND];
+#pragma unroll
+    for (u32 k = 0; k < ORDER_CAND; ++k) acc[k] = 0.f;
+    for (u32 c = lane; c < d / 4; c += 64) {
+        const float4 q = ((const float4*)(qrot + row * d))[c];
+#pragma unroll
+        for (u32 k = 0; k < ORDER_CAND; ++k)
+            if (k < ncand) {
+                const float4 x = ((const float4*)(dirs + (u64)k * d))[c];
+                acc[k] += q.x * x.x + q.y * x.y + q.z * x.z + q.w * x.w;
+            }
+    }
+#pragma unroll
+    for (u32 k = 0; k < ORDER_CAND; ++k) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc[k] += __shfl_xor(acc[k], o, 64);
+        if ((u32)lane == k) proj[row * ORDER_CAND + k] = acc[k];
+    }
+}
+
+// the candidate with the largest variance of the projections per unit length -> *best
+__global__ void __launch_bounds__(1024) k_order_pick(const float* __restrict__ proj, u64 rows, u32 ncand, const float* __restrict__ norm2,
+                                                     u32* __restrict__ best) {
+    __shared__ double s1[1024], s2[1024];
+    const u32 t = threadIdx.x, k = t % ORDER_CAND;
+    double a = 0.0, b = 0.0;
+    for (u64 r = t / ORDER_CAND; r < rows; r += 1024 / ORDER_CAND) {
+        const double v = (double)proj[r * ORDER_CAND + k];
+        a += v; b += v * v;
+    }
+    s1[t] = a; s2[t] = b;
+    __syncthreads();
+    for (u32 step = 512; step >= ORDER_CAND; step >>= 1) {       // threads t and t + step hold the same candidate
+        if (t < step) { s1[t] += s1[t + step]; s2[t] += s2[t + step]; }
+        __syncthreads();
+    }
+    if (t == 0) {
+        u32 arg = 0;
+        double top = -1.0;
+        for (u32 c = 0; c < ncand; ++c) {
+            const double n2 = (double)norm2[c];
+            const double var = n2 > 0.0 ? (s2[c] - s1[c] * s1[c] / (double)rows) / n2 : 0.0;
+            if (var > top) { top = var; arg = c; }
+        }
+        *best = arg;
+    }
+}
+
+__global__ void __launch_bounds__(256) k_order_keys(const float* __restrict__ proj, u64 rows, const u32* __restrict__ best,
+                                                    float* __restrict__ keys, u32* __restrict__ vals) {
+    const u64 r = (u64)blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    keys[r] = proj[r * ORDER_CAND + *best];
+    vals[r] = (u32)r;
+}
+
 }  // namespace
+
+int pag_order_queries(pag_index* ix, const float* qrot, u64 nq, const u32** order) {
+    *order = nullptr;
+    const u32 ncand = std::min<u32>(ORDER_CAND, ix->n_entry);
+    if (ncand == 0 || nq < 2 || nq >= (1ull << 31)) return PAG_OK;
+    hipStream_t s = ix->stream;
+    const u32 d = ix->L.d;
+    size_t sort_bytes = 0;
+    PAG_HIP(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const float*)nullptr, (float*)nullptr, (const u32*)nullptr,
+                                               (u32*)nullptr, (int)nq, 0, 32, s));
+    // words: proj [nq * 16] | keys in [nq] | keys out [nq] | numbers [nq] | order [nq] | dirs [16 * d] | norm2 [16] | best [16] | sort
+    const u64 o_keys = nq * ORDER_CAND, o_keys2 = o_keys + nq, o_vals = o_keys2 + nq, o_order = o_vals + nq, o_dirs = o_order + nq;
+    const u64 o_norm = o_dirs + (u64)ORDER_CAND * d, o_best = o_norm + ORDER_CAND, o_sort = (o_best + 16 + 63) / 64 * 64;   // 256-byte aligned
+    const u64 need = o_sort + (sort_bytes + 3) / 4;
+    if (ix->ws_order_cap < need) {
+        if (ix->ws_order) (void)hipFree(ix->ws_order);
+        ix->ws_order = nullptr; ix->ws_order_cap = 0;
+        hipError_t e = hipMalloc((void**)&ix->ws_order, need * 4);
+        if (e != hipSuccess) { pag_set_error(std::string("hipMalloc (query order): ") + hipGetErrorString(e)); return PAG_ENOMEM; }
+        ix->ws_order_cap = need;
+    }
+    u32* w = ix->ws_order;
+    float* proj = (float*)w;
+    float* dirs = (float*)(w + o_dirs);
+    float* norm2 = (float*)(w + o_norm);
+    hipLaunchKernelGGL(k_order_dirs, dim3(ncand), dim3(64), 0, s, pag_vecs_of(ix), ix->entry, dirs, norm2);
+    hipLaunchKernelGGL(k_order_project, dim3((unsigned)nq), dim3(64), 0, s, qrot, nq, d, dirs, ncand, proj);
+    hipLaunchKernelGGL(k_order_pick, dim3(1), dim3(1024), 0, s, proj, nq, ncand, norm2, w + o_best);
+    hipLaunchKernelGGL(k_order_keys, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, proj, nq, w + o_best, (float*)(w + o_keys),
+                       w + o_vals);
+    PAG_HIP(hipGetLastError());
+    PAG_HIP(hipcub::DeviceRadixSort::SortPairs((void*)(w + o_sort), sort_bytes, (const float*)(w + o_keys), (float*)(w + o_keys2),
+                                               (const u32*)(w + o_vals), w + o_order, (int)nq, 0, 32, s));
+    *order = w + o_order;
+    return PAG_OK;
+}
 
 int pag_launch_rotate(hipStream_t s, const float* X, u64 rows, u32 d, const float* rot, float* out) {
     if (rows == 0) return PAG_OK;

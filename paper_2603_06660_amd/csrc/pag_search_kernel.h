@@ -1068,6 +1068,7 @@ __global__ void __launch_bounds__(64) k_search(const SearchArgs A) {
         if (lane == 0) qi = atomicAdd(A.qcounter, 1u);
         qi = uniform(qi);
         if (qi >= A.nq) break;
+        if (A.order) qi = A.order[qi];
         w.run_query(qi);
     }
     w.flush_stats();
