@@ -86,6 +86,10 @@ typedef struct {
                                   signs) instead of a Haar-distributed rotation.  Still orthogonal, and its products are exact,
                                   so the stored vectors are the input's values bit for bit; it does not mix coordinates, so
                                   it suits data that is already isotropic (and comparisons that must not depend on rounding). */
+#define PAG_FLAG_KEEP_QUERY_ORDER 64u /* search time: the queries of a call are taken as numbered.  By default a call with more
+                                  queries than the GPU keeps waves resident takes them in the order of their projections onto
+                                  the batch's direction of largest spread, so that searches running side by side visit the
+                                  same part of the graph and share rows in the caches.  Results never depend on it. */
 
 /*
  * Flat host view of an index (Alg. 1 output: node set, edge set E, inference
@@ -174,7 +178,7 @@ int pag_search(const pag_index* ix, const float* Q, uint64_t nq, uint32_t K, uin
  * them, nothing is launched): nq * (d + 16 * S [+ d for PAG_COS]) <= 4,194,304 floats, where S is
  * num_subspaces rounded up to 16, 32 or 64; index capacity <= 4,194,304 vectors; working set b <= 128
  * (K <= 128).  With fewer bitmaps than the GPU could keep waves busy the call is slower than pag_search,
- * never different.  All calls on one GPU share the array: calls that overlap in time on one GPU (from
+ * never different; it also takes the queries as numbered (see PAG_FLAG_KEEP_QUERY_ORDER).  All calls on one GPU share the array: calls that overlap in time on one GPU (from
  * any thread, on any index) race and must be serialised by the caller.  The call synchronises the
  * index's stream before it returns, like pag_search.
  */
@@ -212,7 +216,7 @@ int pag_import(const pag_arrays* in, const pag_params* params, pag_index** out);
 int pag_get_counters(const pag_index* ix, pag_counters* out);
 int pag_reset_counters(pag_index* ix);
 /* Changes search-time settings of an existing index: working-set size (0 = max(10,K)) and the search-time
- * PAG_FLAG_* bits (PAG_FLAG_NO_PRT, PAG_FLAG_EXACT_TEST_COUNT); the bits fixed at build time stay. */
+ * PAG_FLAG_* bits (PAG_FLAG_NO_PRT, PAG_FLAG_EXACT_TEST_COUNT, PAG_FLAG_KEEP_QUERY_ORDER); the bits fixed at build time stay. */
 int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t flags);
 /* log2 of the slots of the per-query LDS seen-set table; 0 = choose from efS.  Small values exercise the HBM spill path. */
 int pag_set_seen_capacity_log2(pag_index* ix, uint32_t log2_slots);

@@ -10,4 +10,4 @@ the first use does, and raises if it has not been built.
 """
 from .binding import (PagIndex, PagError, load_library, library_path, EXPORTED_SYMBOLS,  # noqa: F401
                       L2, IP, COS, FLAG_NO_PRT, FLAG_NO_PES, FLAG_FP16_VECTORS, FLAG_KEEP_ORDER,
-                      FLAG_EXACT_TEST_COUNT, FLAG_PERMUTATION_TRANSFORM)
+                      FLAG_EXACT_TEST_COUNT, FLAG_PERMUTATION_TRANSFORM, FLAG_KEEP_QUERY_ORDER)

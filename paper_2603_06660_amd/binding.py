@@ -16,6 +16,7 @@ FLAG_FP16_VECTORS = 4
 FLAG_KEEP_ORDER = 8
 FLAG_EXACT_TEST_COUNT = 16
 FLAG_PERMUTATION_TRANSFORM = 32
+FLAG_KEEP_QUERY_ORDER = 64
 _METRICS = {"l2": L2, "ip": IP, "cos": COS, "cosine": COS, L2: L2, IP: IP, COS: COS}
 
 EXPORTED_SYMBOLS = (

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <mutex>
@@ -561,7 +562,7 @@ extern "C" int pag_set_search_options(pag_index* ix, uint32_t search_b, uint32_t
     PAG_CHECK(ix, PAG_EINVAL, "null argument");
     PAG_CHECK(search_b <= PAG_MAX_B, PAG_EUNSUPPORTED, "search_b above 1024 is not built");
     ix->search_b = search_b;
-    const u32 search_bits = PAG_FLAG_NO_PRT | PAG_FLAG_EXACT_TEST_COUNT;
+    const u32 search_bits = PAG_FLAG_NO_PRT | PAG_FLAG_EXACT_TEST_COUNT | PAG_FLAG_KEEP_QUERY_ORDER;
     ix->flags = (ix->flags & ~search_bits) | (flags & search_bits);           // index-time bits stay as built
     return PAG_OK;
 }
@@ -704,7 +705,7 @@ static int search_impl(pag_index* ix, const float* Q, uint64_t nq, uint32_t K, u
     PAG_HIP(hipEventRecord(ix->ev[0], ix->stream));
     if ((rc = prepare(ix, Q, nq, ix->ws_qrot, ix->ws_tab))) return rc;
     // more queries than resident waves: those that run side by side are chosen to be neighbours
-    if (nq > (u64)grid && (rc = pag_order_queries(ix, ix->ws_qrot, nq, &a.order))) return rc;
+    if (!(ix->flags & PAG_FLAG_KEEP_QUERY_ORDER) && nq > (u64)grid && (rc = pag_order_queries(ix, ix->ws_qrot, nq, &a.order))) return rc;
     if ((rc = pag_launch_zero_u32(ix->stream, ix->d_qcounter, 1))) return rc;
     PAG_HIP(hipEventRecord(ix->ev[1], ix->stream));
     if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;

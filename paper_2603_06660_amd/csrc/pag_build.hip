@@ -569,7 +569,7 @@ static int search_candidates(pag_index* ix, BuildWs& ws, const float* qrot, u64 
     a.cand = ws.cand; a.cand_cnt = ws.cand_cnt; a.cand_cap = cand_cap;
     a.pes = ws.pes;
     // more points than resident waves: those that search side by side are chosen to be neighbours
-    if (m > (u64)grid && (rc = pag_order_queries(ix, qrot, m, &a.order))) return rc;
+    if (!(ix->flags & PAG_FLAG_KEEP_QUERY_ORDER) && m > (u64)grid && (rc = pag_order_queries(ix, qrot, m, &a.order))) return rc;
     if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
     if (ws.ev[0]) PAG_HIP(hipEventRecord(ws.ev[0], s));
     if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;

@@ -130,9 +130,9 @@ __global__ void __launch_bounds__(256) k_zero_u32(u32* p, u64 count) {
 // ---------------------------------------------------------------------------------------
 // Query order.  The waves take the queries of a batch a few thousand at a time; when the queries that run side by
 // side search the same part of the graph, part of their rows comes from the memory-side cache instead of HBM.  The
-// batch is therefore taken in the order of its projections onto one direction: of ORDER_CAND stored vectors (the
-// first entry nodes, i.e. random data points), the one along which the batch varies most.  Results do not depend
-// on the order.
+// batch is therefore taken in the order of its projections onto its direction of largest spread, found by two steps
+// of the power iteration from the best of ORDER_CAND stored vectors (the first entry nodes, i.e. random data
+// points: the one along which the batch varies most).  Results do not depend on the order.
 // ---------------------------------------------------------------------------------------
 constexpr u32 ORDER_CAND = 16;
 
@@ -180,7 +180,7 @@ __global__ void __launch_bounds__(64) k_order_project(const float* __restrict__ 
 
 // the candidate with the largest variance of the projections per unit length -> *best
 __global__ void __launch_bounds__(1024) k_order_pick(const float* __restrict__ proj, u64 rows, u32 ncand, const float* __restrict__ norm2,
-                                                     u32* __restrict__ best) {
+                                                     u32* __restrict__ best, float* __restrict__ pbar) {
     __shared__ double s1[1024], s2[1024];
     const u32 t = threadIdx.x, k = t % ORDER_CAND;
     double a = 0.0, b = 0.0;
@@ -203,6 +203,7 @@ __global__ void __launch_bounds__(1024) k_order_pick(const float* __restrict__ p
             if (var > top) { top = var; arg = c; }
         }
         *best = arg;
+        *pbar = (float)(s1[arg] / (double)rows);
     }
 }
 
@@ -212,6 +213,65 @@ __global__ void __launch_bounds__(256) k_order_keys(const float* __restrict__ pr
     if (r >= rows) return;
     keys[r] = proj[r * ORDER_CAND + *best];
     vals[r] = (u32)r;
+}
+
+// One step of the power iteration towards the batch's direction of largest spread: v' = sum_i (p_i - pbar) q_i, the
+// centred batch applied to its own projections (the sum of the weights is zero, so the mean of the batch drops out).
+// k_order_back: partial sums over ORDER_CHUNKS row chunks, one column per thread, together with the column sums of
+// the batch; k_order_finish: v' and the mean of the next projections, <mean row, v'>.
+constexpr u32 ORDER_CHUNKS = 64;
+
+__global__ void __launch_bounds__(256) k_order_back(const float* __restrict__ qrot, u64 rows, u32 d, const float* __restrict__ p,
+                                                    const float* __restrict__ pbar, float* __restrict__ part_v,
+                                                    float* __restrict__ part_m) {
+    const u32 j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= d) return;
+    const u64 per = (rows + ORDER_CHUNKS - 1) / ORDER_CHUNKS;
+    const u64 r0 = (u64)blockIdx.y * per, r1 = r0 + per < rows ? r0 + per : rows;
+    const float mean = *pbar;
+    float av = 0.f, am = 0.f;
+    for (u64 r = r0; r < r1; ++r) {
+        const float x = qrot[r * d + j];
+        av += (p[r] - mean) * x;
+        am += x;
+    }
+    part_v[(u64)blockIdx.y * d + j] = av;
+    part_m[(u64)blockIdx.y * d + j] = am;
+}
+
+__global__ void __launch_bounds__(1024) k_order_finish(const float* __restrict__ part_v, const float* __restrict__ part_m, u64 rows, u32 d,
+                                                       float* __restrict__ v, float* __restrict__ pbar) {
+    __shared__ double red[1024];
+    double dot = 0.0;
+    for (u32 j = threadIdx.x; j < d; j += 1024) {
+        double a = 0.0, m = 0.0;
+        for (u32 c = 0; c < ORDER_CHUNKS; ++c) { a += (double)part_v[(u64)c * d + j]; m += (double)part_m[(u64)c * d + j]; }
+        v[j] = (float)a;
+        dot += (double)(float)a * (m / (double)rows);
+    }
+    red[threadIdx.x] = dot;
+    __syncthreads();
+    for (u32 step = 512; step > 0; step >>= 1) {
+        if (threadIdx.x < step) red[threadIdx.x] += red[threadIdx.x + step];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *pbar = (float)red[0];
+}
+
+// p[row] = <q_row, v>, one wave per row
+__global__ void __launch_bounds__(64) k_order_project1(const float* __restrict__ qrot, u64 rows, u32 d, const float* __restrict__ v,
+                                                       float* __restrict__ p) {
+    const u64 row = blockIdx.x;
+    if (row >= rows) return;
+    float acc = 0.f;
+    for (u32 c = threadIdx.x; c < d / 4; c += 64) {
+        const float4 q = ((const float4*)(qrot + row * d))[c];
+        const float4 x = ((const float4*)v)[c];
+        acc += q.x * x.x + q.y * x.y + q.z * x.z + q.w * x.w;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (threadIdx.x == 0) p[row] = acc;
 }
 
 }  // namespace
@@ -225,9 +285,11 @@ int pag_order_queries(pag_index* ix, const float* qrot, u64 nq, const u32** orde
     size_t sort_bytes = 0;
     PAG_HIP(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const float*)nullptr, (float*)nullptr, (const u32*)nullptr,
                                                (u32*)nullptr, (int)nq, 0, 32, s));
-    // words: proj [nq * 16] | keys in [nq] | keys out [nq] | numbers [nq] | order [nq] | dirs [16 * d] | norm2 [16] | best [16] | sort
+    // words: proj [nq * 16] | keys in [nq] | keys out [nq] | numbers [nq] | order [nq] | dirs [16 * d] | norm2 [16] |
+    //        best, mean [16] | v [d] | partial sums [2 * 64 * d] | sort
     const u64 o_keys = nq * ORDER_CAND, o_keys2 = o_keys + nq, o_vals = o_keys2 + nq, o_order = o_vals + nq, o_dirs = o_order + nq;
-    const u64 o_norm = o_dirs + (u64)ORDER_CAND * d, o_best = o_norm + ORDER_CAND, o_sort = (o_best + 16 + 63) / 64 * 64;   // 256-byte aligned
+    const u64 o_norm = o_dirs + (u64)ORDER_CAND * d, o_best = o_norm + ORDER_CAND, o_v = o_best + 16, o_part = o_v + d;
+    const u64 o_sort = (o_part + 2ull * ORDER_CHUNKS * d + 63) / 64 * 64;   // 256-byte aligned
     const u64 need = o_sort + (sort_bytes + 3) / 4;
     if (ix->ws_order_cap < need) {
         if (ix->ws_order) (void)hipFree(ix->ws_order);
@@ -242,9 +304,19 @@ int pag_order_queries(pag_index* ix, const float* qrot, u64 nq, const u32** orde
     float* norm2 = (float*)(w + o_norm);
     hipLaunchKernelGGL(k_order_dirs, dim3(ncand), dim3(64), 0, s, pag_vecs_of(ix), ix->entry, dirs, norm2);
     hipLaunchKernelGGL(k_order_project, dim3((unsigned)nq), dim3(64), 0, s, qrot, nq, d, dirs, ncand, proj);
-    hipLaunchKernelGGL(k_order_pick, dim3(1), dim3(1024), 0, s, proj, nq, ncand, norm2, w + o_best);
-    hipLaunchKernelGGL(k_order_keys, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, proj, nq, w + o_best, (float*)(w + o_keys),
-                       w + o_vals);
+    float* pbar = (float*)(w + o_best + 1);
+    float* keys = (float*)(w + o_keys);
+    float* v = (float*)(w + o_v);
+    float* part_v = (float*)(w + o_part);
+    float* part_m = part_v + (u64)ORDER_CHUNKS * d;
+    hipLaunchKernelGGL(k_order_pick, dim3(1), dim3(1024), 0, s, proj, nq, ncand, norm2, w + o_best, pbar);
+    hipLaunchKernelGGL(k_order_keys, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, proj, nq, w + o_best, keys, w + o_vals);
+    // two steps from the best stored vector reach the direction of largest spread to within a percent of its variance
+    for (int it = 0; it < 2; ++it) {
+        hipLaunchKernelGGL(k_order_back, dim3((d + 255) / 256, ORDER_CHUNKS), dim3(256), 0, s, qrot, nq, d, keys, pbar, part_v, part_m);
+        hipLaunchKernelGGL(k_order_finish, dim3(1), dim3(1024), 0, s, part_v, part_m, nq, d, v, pbar);
+        hipLaunchKernelGGL(k_order_project1, dim3((unsigned)nq), dim3(64), 0, s, qrot, nq, d, v, keys);
+    }
     PAG_HIP(hipGetLastError());
     PAG_HIP(hipcub::DeviceRadixSort::SortPairs((void*)(w + o_sort), sort_bytes, (const float*)(w + o_keys), (float*)(w + o_keys2),
                                                (const u32*)(w + o_vals), w + o_order, (int)nq, 0, 32, s));

@@ -155,6 +155,33 @@ def test_search_is_deterministic(cfg1_small, imported):
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
+def test_more_queries_than_resident_waves(orc, cfg1_small, cfg1_oracle_index, imported):
+    """A batch larger than the number of resident waves is taken in the library's own order (projections onto the
+    batch's direction of largest spread): the answers are those of the batch taken as numbered, bit for bit, and the
+    oracle's; the counters do not change either."""
+    from paper_2603_06660_amd import FLAG_KEEP_QUERY_ORDER
+    w, base, q, gt, gtk = cfg1_small
+    rng = np.random.default_rng(17)
+    many = wl.make(wl.workload(1, n=3000, nq=9000), "query")
+    many = many[rng.permutation(len(many))]
+    qd = torch.from_numpy(many).cuda()
+    imported.reset_counters()
+    a = imported.search(qd, w.K, 48)
+    ca = imported.counters()
+    imported.set_search_options(0, FLAG_KEEP_QUERY_ORDER)
+    try:
+        imported.reset_counters()
+        b = imported.search(qd, w.K, 48)
+        cb = imported.counters()
+    finally:
+        imported.set_search_options(0, 0)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    for k in ("queries", "hops", "tests", "passes", "exact", "rounds"):
+        assert ca[k] == cb[k], k
+    oi, od, _ = cfg1_oracle_index.search(many[:300], w.K, 48)
+    assert (a[0][:300].cpu().numpy() == oi).mean() >= 0.999
+
+
 def test_seen_set_spill_path(orc, cfg1_small, cfg1_oracle_index, imported):
     """A 64-slot LDS seen set overflows at once: the HBM bitmap must keep the search exact."""
     w, base, q, gt, gtk = cfg1_small
