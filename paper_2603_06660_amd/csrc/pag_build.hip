@@ -196,10 +196,13 @@ template <int NQ, int C, int G, int NB>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 4)))
 k_prune(pag_vecs vec, uint8_t* __restrict__ recs, pag_layout L, const u32* __restrict__ nodes, u32 m,
             const u64* __restrict__ cand_sorted, const u32* __restrict__ cand_cnt, u32 cand_cap, u32 efC, u32 J,
-            const u64* __restrict__ pes, float* __restrict__ e2, u64* __restrict__ rev_keys, u32* __restrict__ rev_vals) {
+            const u64* __restrict__ pes, float* __restrict__ e2, u64* __restrict__ rev_keys, u32* __restrict__ rev_vals,
+            const u32* __restrict__ taken) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const u32 vi = blockIdx.x;
-    if (vi >= m) return;
+    if (blockIdx.x >= m) return;
+    // nodes pruned side by side are neighbours when the insertion search took them in its own order: their
+    // candidate lists overlap, and so do the rows they fetch
+    const u32 vi = taken ? taken[blockIdx.x] : blockIdx.x;
     const int lane = threadIdx.x;
     u32* kept = (u32*)(smem + (size_t)J * NQ * 1024);       // [deg]
     const PruneRows<NQ, C, G> P{vec, L.d / 4, lane, (float4*)smem};
@@ -347,7 +350,7 @@ k_prune(pag_vecs vec, uint8_t* __restrict__ recs, pag_layout L, const u32* __res
 
 template <int NQ>
 static int launch_prune(hipStream_t s, const pag_index* ix, const u32* nodes, u32 m, const u64* cand_sorted,
-                        const u32* cand_cnt, u32 cand_cap, const u64* pes, u64* rev_keys, u32* rev_vals) {
+                        const u32* cand_cnt, u32 cand_cap, const u64* pes, u64* rev_keys, u32* rev_vals, const u32* taken) {
     const pag_layout& L = ix->L;
     // kept rows held in LDS (slots of NQ KB): four, more while they fit 16 KB, fewer beyond 36 KB.  Measured on
     // 1M x 768 / 1024 / 1536 and 250k x 3072: 16 / 16 / 24 / 36 KB are the fastest; larger sets lose more waves than
@@ -357,7 +360,7 @@ static int launch_prune(hipStream_t s, const pag_index* ix, const u32* nodes, u3
     J = std::min<u32>(J, L.deg);
     const u32 lds = J * NQ * 1024u + L.deg * 4;
     hipLaunchKernelGGL((k_prune<NQ, 2, 2, 2>), dim3(m), dim3(64), lds, s, pag_vecs_of(ix), ix->rec, L, nodes, m, cand_sorted,
-                       cand_cnt, cand_cap, ix->efC, J, pes, ix->e2, rev_keys, rev_vals);
+                       cand_cnt, cand_cap, ix->efC, J, pes, ix->e2, rev_keys, rev_vals, taken);
     PAG_HIP(hipGetLastError());
     return PAG_OK;
 }
@@ -517,6 +520,7 @@ struct BuildWs {
     u64 *rk_in = nullptr, *rk_out = nullptr; u32 *rv_in = nullptr, *rv_out = nullptr;
     u32* edges = nullptr; u32* n_edges = nullptr;
     u32* order = nullptr;
+    const u32* taken = nullptr;    // the order in which the last insertion search took its points (null: as listed)
     u32* density = nullptr;
     void* sort_tmp = nullptr; size_t sort_bytes = 0;
     int *seg_begin = nullptr, *seg_end = nullptr;
@@ -570,6 +574,7 @@ static int search_candidates(pag_index* ix, BuildWs& ws, const float* qrot, u64 
     a.pes = ws.pes;
     // more points than resident waves: those that search side by side are chosen to be neighbours
     if (!(ix->flags & PAG_FLAG_KEEP_QUERY_ORDER) && m > (u64)grid && (rc = pag_order_queries(ix, qrot, m, &a.order))) return rc;
+    ws.taken = a.order;
     if ((rc = pag_launch_zero_u32(s, ix->d_qcounter, 1))) return rc;
     if (ws.ev[0]) PAG_HIP(hipEventRecord(ws.ev[0], s));
     if ((rc = pag_launch_search(ix, a, lds, &grid))) return rc;
@@ -684,7 +689,7 @@ int pag_build_range(pag_index* ix, u64 n_begin, u64 n_end) {
         if ((rc = search_candidates(ix, ws, ix->ws_qrot, m, b, cand_cap, n_end))) return rc;
         //    RobustPrune -> N_out(v), reverse pairs
         {
-#define PRUNE_ARGS s, ix, nodes, (u32)m, ws.cand_sorted, ws.cand_cnt, cand_cap, ws.pes, ws.rk_in, ws.rv_in
+#define PRUNE_ARGS s, ix, nodes, (u32)m, ws.cand_sorted, ws.cand_cnt, cand_cap, ws.pes, ws.rk_in, ws.rv_in, ws.taken
             const u32 nq = (L.d / 4 + 63) / 64;          // 16-byte chunks of a row per lane
             if (nq <= 1) rc = launch_prune<1>(PRUNE_ARGS);
             else if (nq == 2) rc = launch_prune<2>(PRUNE_ARGS);
